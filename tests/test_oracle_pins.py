@@ -1,0 +1,467 @@
+"""Pins for the CPU oracle: every check compares it with something other than itself.
+
+Each pin names what fixes the expected value (paper: arxiv 2208.11580):
+
+* closed-form least squares on the surviving support (Sec. 3 eq. (2); Sec. 4 Step 2: a row's
+  final weights depend only on which weights were removed; OBS formulas are exact, Sec. 3),
+  solved on H with numpy, never touching H^-1
+* the loss identity  sum_t dL_t = 1/2 (w - w_hat)^T H (w - w_hat) = ||w X - w_hat X||^2
+* brute force over every candidate, d <= 8 (the greedy choice of eq. (3) / eq. (7))
+* Lemma 1 against direct inversion of the reduced Hessian
+* quant(.) == 0 reduces OBQ to pruning (Sec. 5, after eq. (7))
+* a diagonal Hessian reduces everything to textbook routines (magnitude pruning,
+  round-to-nearest, top-N per block, global magnitude pruning)
+* Appendix Algorithm 2 equals OBS run on the whole matrix (Sec. 4 Step 2)
+* invariances (H -> cH, column permutation)
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+RTOL = 1e-9
+
+
+def _problem(seed, d, n=None, R=1, damp=0.01, cond=30.0):
+    rng = np.random.default_rng(seed)
+    n = n or 4 * d
+    A = rng.standard_normal((d, d)) @ np.diag(np.logspace(0, -np.log10(cond), d))
+    X = A @ rng.standard_normal((d, n))
+    W = rng.standard_normal((R, d)) * 0.1
+    return W, X
+
+
+def _ls_on_support(H, w, fixed_idx, fixed_val):
+    """argmin_v 1/2 (v-w)^T H (v-w)  s.t. v[fixed_idx] = fixed_val, solved on H itself."""
+    d = len(w)
+    P = np.asarray(fixed_idx, dtype=int)
+    S = np.setdiff1d(np.arange(d), P)
+    v = np.zeros(d)
+    v[P] = fixed_val
+    if S.size:
+        # stationarity on the free block: H_SS (v_S - w_S) + H_SP (v_P - w_P) = 0
+        v[S] = w[S] - np.linalg.solve(H[np.ix_(S, S)], H[np.ix_(S, P)] @ (v[P] - w[P]))
+    return v
+
+
+def _quad(H, a, b):
+    e = a - b
+    return 0.5 * e @ H @ e
+
+
+# ----------------------------------------------------------------------------- Hessian, inverse
+def test_hessian_is_twice_sum_of_outer_products(orc):
+    rng = np.random.default_rng(1)
+    X = rng.standard_normal((5, 11)).astype(np.float32)
+    H0 = np.zeros((5, 5))
+    for n in range(X.shape[1]):
+        x = X[:, n].astype(np.float64)
+        H0 += 2.0 * np.outer(x, x)
+    assert np.allclose(orc.hessian(X, damp_rel=-1), H0, rtol=1e-13, atol=0)
+    lam = 0.01 * np.mean(np.diag(H0))
+    assert np.allclose(orc.hessian(X, damp_rel=0.01), H0 + lam * np.eye(5), rtol=1e-13, atol=0)
+
+
+def test_hessian_is_the_hessian_of_the_row_loss(orc):
+    # second finite difference of f(v) = ||v X - w X||^2 along random directions equals u^T H u
+    rng = np.random.default_rng(2)
+    X = rng.standard_normal((6, 40))
+    H = orc.hessian(X, damp_rel=-1)
+    w = rng.standard_normal(6)
+    f = lambda v: np.sum(((v - w) @ X) ** 2)
+    for _ in range(4):
+        u = rng.standard_normal(6)
+        h = 1e-3
+        second = (f(w + h * u) - 2 * f(w) + f(w - h * u)) / h**2
+        assert np.isclose(second, u @ H @ u, rtol=1e-6)
+
+
+def test_inverse_matches_lapack_and_identity(orc):
+    for d in (1, 2, 7, 33, 96):
+        _, X = _problem(10 + d, d)
+        H = orc.hessian(X)
+        A = orc.invert(H)
+        assert np.allclose(A, A.T, rtol=0, atol=0)
+        assert np.allclose(A @ H, np.eye(d), atol=1e-8)
+        assert np.allclose(A, np.linalg.inv(H), rtol=1e-7, atol=1e-12 * np.abs(A).max())
+
+
+def test_inverse_rejects_non_spd(orc):
+    H = np.array([[1.0, 2.0], [2.0, 1.0]])
+    with pytest.raises(orc.OracleError) as e:
+        orc.invert(H)
+    assert e.value.code == orc.ORC_NOT_SPD
+
+
+# ----------------------------------------------------------------------------- P1 closed form
+@pytest.mark.parametrize("d,k", [(6, 3), (24, 24), (40, 17), (64, 50)])
+def test_pruned_row_equals_least_squares_on_support(orc, d, k):
+    W, X = _problem(100 + d, d)
+    H = orc.hessian(X)
+    r = orc.prune_row(orc.invert(H), W[0], k_steps=k, want_trace=True)
+    assert len(set(r.order.tolist())) == k
+    for t in (0, k // 2, k - 1):
+        P = r.order[: t + 1]
+        ref = _ls_on_support(H, W[0], P, np.zeros(len(P)))
+        assert np.allclose(r.trace[t], ref, rtol=1e-7, atol=1e-10)
+        assert np.all(r.trace[t][P] == 0.0)
+    assert np.array_equal(r.trace[k - 1], r.w)
+
+
+def test_nm_row_equals_least_squares_and_pattern(orc):
+    d = 32
+    W, X = _problem(7, d)
+    H = orc.hessian(X)
+    for (n, m) in ((2, 4), (4, 8), (1, 4)):
+        r = orc.prune_row(orc.invert(H), W[0], nm=(n, m))
+        assert len(r.order) == d // m * (m - n)
+        zeros = (r.w == 0.0).reshape(-1, m).sum(axis=1)
+        assert np.all(zeros == m - n)
+        ref = _ls_on_support(H, W[0], r.order, np.zeros(len(r.order)))
+        assert np.allclose(r.w, ref, rtol=1e-7, atol=1e-10)
+
+
+def test_quantized_row_free_weights_are_least_squares(orc):
+    d, k = 20, 9
+    W, X = _problem(8, d)
+    H = orc.hessian(X)
+    grid = orc.minmax_grid(W[0], 3)
+    r = orc.quant_row(orc.invert(H), W[0], grid, k_steps=k)
+    P = r.order
+    ref = _ls_on_support(H, W[0], P, r.w[P])
+    assert np.allclose(r.w, ref, rtol=1e-7, atol=1e-10)
+
+
+# ----------------------------------------------------------------------------- P2 loss identity
+@pytest.mark.parametrize("mode", ["prune", "nm", "quant"])
+def test_loss_trace_sums_to_quadratic_form_and_output_error(orc, mode):
+    d = 28
+    W, X = _problem(21, d, n=3 * d)
+    w = W[0]
+    for damp in (-1, 0.01):
+        H = orc.hessian(X, damp_rel=damp)
+        A = orc.invert(H)
+        if mode == "prune":
+            r = orc.prune_row(A, w, k_steps=19)
+        elif mode == "nm":
+            r = orc.prune_row(A, w, nm=(2, 4))
+        else:
+            r = orc.quant_row(A, w, orc.minmax_grid(w, 2))
+        assert np.all(r.loss >= 0)
+        assert np.isclose(r.loss.sum(), _quad(H, w, r.w), rtol=1e-8)
+        if damp < 0:
+            direct = np.sum((w @ X - r.w @ X) ** 2)
+            assert np.isclose(r.loss.sum(), direct, rtol=1e-8)
+
+
+def test_each_loss_change_is_the_step_increase_of_the_quadratic(orc):
+    d = 12
+    W, X = _problem(22, d)
+    H = orc.hessian(X)
+    r = orc.prune_row(orc.invert(H), W[0], want_trace=True)
+    prev = W[0]
+    total = 0.0
+    for t in range(d):
+        now = _quad(H, W[0], r.trace[t])
+        assert np.isclose(now - total, r.loss[t], rtol=1e-6, atol=1e-12)
+        total = now
+        prev = r.trace[t]
+
+
+# ----------------------------------------------------------------------------- P3 brute force
+@pytest.mark.parametrize("seed", range(6))
+def test_greedy_choice_matches_brute_force_pruning(orc, seed):
+    d = 5 + seed % 4  # 5..8
+    W, X = _problem(300 + seed, d)
+    H = orc.hessian(X)
+    w0 = W[0]
+    r = orc.prune_row(orc.invert(H), w0, want_trace=True)
+    removed = []
+    base = 0.0
+    for t in range(d):
+        best, best_cost = None, None
+        for p in range(d):
+            if p in removed:
+                continue
+            v = _ls_on_support(H, w0, removed + [p], np.zeros(len(removed) + 1))
+            cost = _quad(H, w0, v)
+            if best is None or cost < best_cost:
+                best, best_cost = p, cost
+        assert r.order[t] == best
+        assert np.isclose(r.loss[t], best_cost - base, rtol=1e-6, atol=1e-13)
+        removed.append(best)
+        base = best_cost
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_greedy_choice_matches_brute_force_quantization(orc, seed):
+    d = 5 + seed % 4
+    W, X = _problem(400 + seed, d)
+    H = orc.hessian(X)
+    w0 = W[0]
+    delta, offset, maxq = orc.minmax_grid(w0, 2)
+    r = orc.quant_row(orc.invert(H), w0, (delta, offset, maxq), want_trace=True)
+    fixed, vals = [], []
+    cur = w0.copy()
+    base = 0.0
+    for t in range(d):
+        best, best_cost, best_q = None, None, None
+        for p in range(d):
+            if p in fixed:
+                continue
+            # quantize the *current* value of weight p (numpy's rint is half-to-even)
+            q = offset + delta * float(np.clip(np.rint((cur[p] - offset) / delta), 0, maxq))
+            v = _ls_on_support(H, w0, fixed + [p], np.array(vals + [q]))
+            cost = _quad(H, w0, v)
+            if best is None or cost < best_cost:
+                best, best_cost, best_q = p, cost, q
+        assert r.order[t] == best
+        assert np.isclose(r.loss[t], best_cost - base, rtol=1e-6, atol=1e-13)
+        fixed.append(best)
+        vals.append(best_q)
+        cur = _ls_on_support(H, w0, fixed, np.array(vals))
+        assert np.allclose(r.trace[t], cur, rtol=1e-7, atol=1e-10)
+        base = best_cost
+
+
+# ----------------------------------------------------------------------------- P4 Lemma 1
+def test_reduced_inverse_equals_inverse_of_reduced_hessian(orc):
+    d, k = 30, 13
+    W, X = _problem(31, d)
+    H = orc.hessian(X)
+    r = orc.prune_row(orc.invert(H), W[0], k_steps=k)
+    M = np.flatnonzero(r.live)
+    assert len(M) == d - k and set(M) == set(range(d)) - set(r.order.tolist())
+    direct = np.linalg.inv(H[np.ix_(M, M)])
+    assert np.allclose(r.A[np.ix_(M, M)], direct, rtol=1e-7, atol=1e-12 * np.abs(direct).max())
+
+
+def test_lemma1_single_removal_on_nonsymmetric_matrix(orc):
+    # Lemma 1 holds for any invertible matrix; a symmetric example would hide a transposed operand.
+    # Feed a non-symmetric "inverse" and check the oracle's elimination against direct inversion.
+    rng = np.random.default_rng(5)
+    d = 6
+    Hn = rng.standard_normal((d, d)) + 4 * np.eye(d)
+    Hn_inv = np.linalg.inv(Hn)
+    # make index 2 the first pick: every weight is 1 except a zero at index 2 (score 0)
+    w = np.ones(d)
+    w[2] = 0.0
+    r = orc.prune_row(Hn_inv + 0.0, w, k_steps=1)
+    # the positive-diagonal requirement may not hold for a random matrix; choose one where it does
+    assert r.order[0] == 2
+    M = [0, 1, 3, 4, 5]
+    direct = np.linalg.inv(Hn[np.ix_(M, M)])
+    assert np.allclose(r.A[np.ix_(M, M)], direct, rtol=1e-9, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------- P5 quant == 0
+def test_obq_with_zero_grid_is_pruning(orc):
+    d = 26
+    W, X = _problem(41, d)
+    A = orc.invert(orc.hessian(X))
+    rp = orc.prune_row(A, W[0])
+    rq = orc.quant_row(A, W[0], (1.0, 0.0, 0))  # single grid point 0
+    assert np.array_equal(rp.order, rq.order)
+    assert np.array_equal(rp.loss, rq.loss)
+    assert np.array_equal(rp.w, rq.w)
+    assert np.all(rq.codes == 0)
+
+
+# ----------------------------------------------------------------------------- P6 diagonal Hessian
+def test_diagonal_hessian_reduces_to_textbook_routines(orc):
+    rng = np.random.default_rng(51)
+    d = 24
+    h = rng.uniform(0.5, 2.0, d)
+    A = np.diag(1.0 / h)
+    w = rng.standard_normal(d)
+    # pruning: ascending h_j w_j^2, no compensation
+    r = orc.prune_row(A, w, k_steps=10)
+    expect = np.argsort(h * w * w, kind="stable")[:10]
+    assert np.array_equal(r.order, expect)
+    keep = np.setdiff1d(np.arange(d), expect)
+    assert np.array_equal(r.w[keep], w[keep]) and np.all(r.w[expect] == 0)
+    assert np.allclose(r.loss, 0.5 * (h * w * w)[expect], rtol=1e-12)
+    # OBQ: round-to-nearest of every weight, independent of order
+    grid = orc.minmax_grid(w, 3)
+    rq = orc.quant_row(A, w, grid)
+    rtn = np.clip(np.rint((w - grid[1]) / grid[0]), 0, grid[2]).astype(int)
+    assert np.array_equal(rq.codes, rtn)
+    assert np.array_equal(rq.w, grid[1] + grid[0] * rtn)
+    # 2:4 with identity Hessian: keep the two largest magnitudes of every block of four
+    r24 = orc.prune_row(np.eye(d), w, nm=(2, 4))
+    for b in range(d // 4):
+        blk = np.abs(w[4 * b : 4 * b + 4])
+        kept = np.flatnonzero(r24.w[4 * b : 4 * b + 4] != 0)
+        assert set(kept) == set(np.argsort(blk)[2:])
+
+
+def test_global_select_with_diagonal_hessian_is_global_magnitude_pruning(orc):
+    rng = np.random.default_rng(52)
+    R, d, k = 5, 12, 23
+    W = rng.standard_normal((R, d))
+    res = orc.prune_rows(np.eye(d), W)
+    counts = orc.global_select(res["loss"], k)
+    mask = orc.mask_from_counts(res["order"], counts, d)
+    thresh = np.sort(np.abs(W).ravel())[k - 1]
+    assert mask.sum() == k
+    assert np.array_equal(mask.astype(bool), np.abs(W) <= thresh)
+
+
+# ----------------------------------------------------------------------------- P7 Algorithm 2
+@pytest.mark.parametrize("seed,k", [(0, 7), (1, 1), (2, 14), (3, 15), (4, 0)])
+def test_global_select_equals_obs_on_the_whole_matrix(orc, seed, k):
+    R, d = 3, 5
+    W, X = _problem(600 + seed, d, R=R)
+    H = orc.hessian(X)
+    A = orc.invert(H)
+    res = orc.prune_rows(A, W, want_trace=True)
+    counts = orc.global_select(res["loss"], k)
+    assert counts.sum() == k
+    # literal OBS on the flattened matrix: block-diagonal Hessian, one weight at a time
+    big = orc.prune_row(np.kron(np.eye(R), A), W.ravel(), k_steps=k)
+    whole_mask = np.zeros(R * d, np.uint8)
+    whole_mask[big.order] = 1
+    assert np.array_equal(orc.mask_from_counts(res["order"], counts, d), whole_mask.reshape(R, d))
+    assert np.allclose(orc.reconstruct(A, W, counts), big.w.reshape(R, d), rtol=1e-8, atol=1e-12)
+    for i in range(R):
+        if counts[i] > 0:
+            assert np.array_equal(orc.reconstruct(A, W, counts)[i], res["trace"][i, counts[i] - 1])
+
+
+def test_global_select_follows_next_loss_not_sorted_losses(orc):
+    # non-monotone traces: Algorithm 2 can only take a row's losses in order
+    L = np.array([[5.0, 1.0, 9.0], [2.0, 8.0, 0.5]])
+    assert orc.global_select(L, 1).tolist() == [0, 1]
+    assert orc.global_select(L, 2).tolist() == [1, 1]   # 5 < 8
+    assert orc.global_select(L, 3).tolist() == [2, 1]   # then the 1 behind the 5
+    assert orc.global_select(L, 4).tolist() == [2, 2]   # 8 < 9
+    assert orc.global_select(L, 5).tolist() == [2, 3]   # 0.5 < 9
+    assert orc.global_select(L, 6).tolist() == [3, 3]
+    # ties go to the lowest row
+    T = np.array([[1.0, 1.0], [1.0, 1.0]])
+    assert orc.global_select(T, 1).tolist() == [1, 0]
+    assert orc.global_select(T, 3).tolist() == [2, 1]
+
+
+# ----------------------------------------------------------------------------- P8 invariances
+def test_scaling_and_permutation_invariance(orc):
+    d = 18
+    W, X = _problem(71, d)
+    H = orc.hessian(X)
+    A = orc.invert(H)
+    w = W[0]
+    r = orc.prune_row(A, w, want_trace=True)
+    c = 4.0  # power of two: exact in floating point
+    rc = orc.prune_row(orc.invert(c * H), w, want_trace=True)
+    assert np.array_equal(r.order, rc.order)
+    assert np.allclose(rc.loss, c * r.loss, rtol=1e-9)
+    assert np.allclose(rc.trace, r.trace, rtol=1e-9, atol=1e-14)
+    perm = np.random.default_rng(3).permutation(d)
+    rp = orc.prune_row(orc.invert(H[np.ix_(perm, perm)]), w[perm], want_trace=True)
+    assert np.array_equal(perm[rp.order], r.order)
+    assert np.allclose(rp.trace, r.trace[:, perm], rtol=1e-8, atol=1e-13)
+    # a grid no weight sits on exactly (the min-max grid has two zero-error ties, which
+    # the lowest-index rule would break differently after a permutation)
+    g = orc.minmax_grid(w, 4)
+    grid = (g[0] * 1.07, g[1] - 0.013, g[2])
+    q = orc.quant_row(A, w, grid)
+    qp = orc.quant_row(orc.invert(H[np.ix_(perm, perm)]), w[perm], grid)
+    assert np.array_equal(perm[qp.order], q.order)
+    assert np.array_equal(qp.codes, q.codes[perm])
+
+
+# ----------------------------------------------------------------------------- P9 / P10
+def test_quantized_codes_lie_on_the_grid(orc):
+    d = 48
+    W, X = _problem(81, d)
+    A = orc.invert(orc.hessian(X))
+    for bits in (2, 3, 4):
+        delta, offset, maxq = orc.minmax_grid(W[0], bits)
+        r = orc.quant_row(A, W[0], (delta, offset, maxq))
+        assert sorted(r.order.tolist()) == list(range(d))
+        assert r.codes.min() >= 0 and r.codes.max() <= maxq
+        assert np.array_equal(r.w, offset + delta * r.codes)
+        assert np.all(np.diff(np.cumsum(r.loss)) >= 0)
+    # OBQ is not plain rounding: with a correlated Hessian at least one code differs from RTN
+    rtn = np.clip(np.rint((W[0] - offset) / delta), 0, maxq).astype(int)
+    assert np.any(rtn != r.codes)
+    # and it does not do worse than RTN on the layer objective
+    H = orc.hessian(X)
+    assert _quad(H, W[0], r.w) <= _quad(H, W[0], offset + delta * rtn) * (1 + 1e-12)
+
+
+def test_quantizer_rounds_half_to_even_and_clamps(orc):
+    assert orc.quant_code(0.5, 1.0, 0.0, 15) == 0
+    assert orc.quant_code(1.5, 1.0, 0.0, 15) == 2
+    assert orc.quant_code(2.5, 1.0, 0.0, 15) == 2
+    assert orc.quant_code(-3.0, 1.0, 0.0, 15) == 0
+    assert orc.quant_code(99.0, 1.0, 0.0, 15) == 15
+    assert orc.quant_code(0.26, 0.1, 0.05, 3) == 2
+    assert orc.minmax_grid(np.array([2.0, 2.0]), 4) == (1.0, 2.0, 15)
+
+
+def test_zero_weight_is_taken_first_with_zero_update(orc):
+    d = 10
+    W, X = _problem(91, d)
+    A = orc.invert(orc.hessian(X))
+    w = W[0].copy()
+    w[6] = 0.0
+    w[3] = 0.0
+    r = orc.prune_row(A, w, k_steps=2, want_trace=True)
+    assert r.order.tolist() == [3, 6]           # both score 0: lowest index first
+    assert np.all(r.loss == 0.0)
+    assert np.array_equal(r.trace[1], w)
+
+
+def test_forced_order_replays_and_reports_scores(orc):
+    d = 14
+    W, X = _problem(95, d)
+    A = orc.invert(orc.hessian(X))
+    r = orc.prune_row(A, W[0])
+    rf = orc.prune_row(A, W[0], forced=r.order)
+    assert np.array_equal(rf.loss, r.loss) and np.array_equal(rf.pick_score, rf.min_score)
+    swapped = r.order.copy()
+    swapped[[0, 1]] = swapped[[1, 0]]
+    rs = orc.prune_row(A, W[0], forced=swapped)
+    assert rs.pick_score[0] > rs.min_score[0]
+    # two steps later the state is the same whatever the order of the two removals
+    assert np.allclose(rs.w, r.w, rtol=1e-9, atol=1e-14)
+
+
+# ----------------------------------------------------------------------------- compound
+def test_compound_row_is_obq_on_the_reduced_problem(orc):
+    d = 24
+    W, X = _problem(97, d)
+    H = orc.hessian(X)
+    A = orc.invert(H)
+    rp = orc.prune_row(A, W[0], nm=(2, 4))
+    w_out, codes, rq = orc.compound_row(H, rp.w, rp.live, 4)
+    S = np.flatnonzero(rp.live)
+    assert np.all(w_out[rp.live == 0] == 0) and np.all(codes[rp.live == 0] == -1)
+    assert np.all(codes[S] >= 0)
+    # continuing Algorithm 3 on the oracle's own reduced inverse (Lemma 1) gives the same run
+    grid = orc.minmax_grid(rp.w[S], 4)
+    cont = orc.quant_row(rp.A[np.ix_(S, S)], rp.w[S], grid)
+    assert np.array_equal(cont.order, rq.order)
+    assert np.array_equal(cont.codes, rq.codes)
+    assert np.allclose(cont.w, rq.w, rtol=1e-9)
+
+
+# ----------------------------------------------------------------------------- rows driver
+def test_rows_driver_equals_single_rows_and_is_deterministic(orc):
+    R, d = 7, 16
+    W, X = _problem(99, d, R=R)
+    A = orc.invert(orc.hessian(X))
+    res = orc.prune_rows(A, W, n_threads=3)
+    res2 = orc.prune_rows(A, W, n_threads=1)
+    assert res["threads"] == 3 and res2["threads"] == 1
+    for i in range(R):
+        r = orc.prune_row(A, W[i])
+        assert np.array_equal(res["order"][i], r.order)
+        assert np.array_equal(res["loss"][i], r.loss)
+    assert np.array_equal(res["order"], res2["order"]) and np.array_equal(res["loss"], res2["loss"])
+    grids = [orc.minmax_grid(W[i], 4) for i in range(R)]
+    q = orc.quant_rows(A, W, [g[0] for g in grids], [g[1] for g in grids], 15)
+    for i in range(R):
+        r = orc.quant_row(A, W[i], grids[i])
+        assert np.array_equal(q["codes"][i], r.codes) and np.array_equal(q["W"][i], r.w)
