@@ -1,0 +1,139 @@
+/*
+ * libobc -- the layer-wise ExactOBS / OBQ solver of "Optimal Brain Compression"
+ * (arxiv 2208.11580) for one AMD MI355X (gfx950).
+ *
+ * Problem (Sec. 3, eq. (2)): for a layer with weights W (d_row x d_col) and calibration
+ * inputs X (d_col x N) find compressed weights W^ minimising ||W X - W^ X||^2 under a
+ * sparsity or quantization constraint.  The path is
+ *
+ *     X --obc_hessian--> H = 2 X X^T + lambda I --obc_invert--> H^-1
+ *       --obc_prune_rows / obc_quant_rows--> per-row order P, loss changes L, weights
+ *       --obc_global_select--> per-row counts and layer mask --obc_gather_trace--> W^
+ *
+ * Conventions
+ *  - Every array argument is a DEVICE pointer owned by the caller, row-major and
+ *    contiguous unless a leading dimension is given.  `const` inputs are never written.
+ *    The library allocates no large memory: scratch is a caller-provided workspace whose
+ *    size comes from the matching *_workspace_bytes query (host call, no GPU work).
+ *  - All work is enqueued on the HIP stream given to obc_create and is asynchronous with
+ *    respect to the host, except obc_invert and obc_check, which wait for the stream.
+ *  - Every call returns 0 (OBC_OK) or a negative OBC_ERR_* code; nothing throws or aborts
+ *    across this boundary.  obc_last_error gives a text for the last failure on a context.
+ *    Conditions only a kernel can see (a non-positive or non-finite pivot [H^-1]_pp) are
+ *    latched on the device and reported by obc_check.
+ *  - Results are deterministic: the same inputs give bit-identical outputs.
+ *  - Arithmetic is fp32 (obc_invert factorises in fp64 internally and rounds the result).
+ */
+#ifndef OBC_H
+#define OBC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define OBC_OK 0
+#define OBC_ERR_BAD_ARG (-1)   /* null pointer, negative size, value out of range */
+#define OBC_ERR_BAD_SHAPE (-2) /* sizes inconsistent with each other (d % M != 0, k > d, ...) */
+#define OBC_ERR_NOT_SPD (-3)   /* obc_invert met a non-positive Cholesky pivot */
+#define OBC_ERR_WORKSPACE (-4) /* workspace missing or smaller than the query says */
+#define OBC_ERR_NUMERIC (-5)   /* a row solver met a non-positive / non-finite [H^-1]_pp */
+#define OBC_ERR_HIP (-6)       /* a HIP runtime call failed */
+
+/* Row-solver strategies (argument `strategy` below).  AUTO picks LDS-resident rank-1 for
+ * small d_col and the blocked solver otherwise. */
+#define OBC_STRATEGY_AUTO 0
+#define OBC_STRATEGY_RANK1 1   /* literal Algorithm 1: one rank-1 elimination per step */
+#define OBC_STRATEGY_BLOCKED 2 /* same arithmetic result, eliminations applied in blocks */
+
+typedef struct obc_ctx obc_ctx;
+
+/* Create a context bound to `hip_stream` (a hipStream_t; NULL = the default stream) on the
+ * current device.  The context owns only a few bytes of device memory (the error latch). */
+int obc_create(obc_ctx **ctx, void *hip_stream);
+int obc_destroy(obc_ctx *ctx);
+const char *obc_last_error(const obc_ctx *ctx);
+const char *obc_version(void);
+
+/* Wait for the context's stream and return the first error a kernel latched since the last
+ * obc_check (OBC_ERR_NUMERIC, OBC_ERR_NOT_SPD) or OBC_OK; clears the latch. */
+int obc_check(obc_ctx *ctx);
+
+/* ---- Sec. 4: H = 2 X X^T, "Implementation Details": dampening -------------------------
+ * X: d x N fp32 with leading dimension ldx >= N (element (j, n) at X[j*ldx + n]).
+ * H: d x d fp32.  accumulate == 0: H = 2 X X^T;  accumulate != 0: H += 2 X X^T (calibration
+ * data arriving in batches; samples only ever need to be accumulated once).
+ * damp_rel >= 0: after the product, add damp_rel * mean(diag(H)) to the diagonal (call with
+ * damp_rel < 0 for all batches but the last).  The sum over samples is not divided by N. */
+int obc_hessian_workspace_bytes(int d, int64_t N, size_t *bytes);
+int obc_hessian(obc_ctx *ctx, const float *X, int d, int64_t N, int64_t ldx, float damp_rel,
+                int accumulate, float *H, void *ws, size_t ws_bytes);
+
+/* ---- Sec. 4 Step 1: the inverse every row starts from ---------------------------------
+ * In-place inverse of the symmetric positive definite d x d matrix H through its Cholesky
+ * factor (fp64 inside, result rounded to fp32 and exactly symmetric).  Synchronous.
+ * Returns OBC_ERR_NOT_SPD (H is then undefined) when a pivot is not positive. */
+int obc_invert_workspace_bytes(int d, size_t *bytes);
+int obc_invert(obc_ctx *ctx, float *H_inout, int d, void *ws, size_t ws_bytes);
+
+/* ---- Algorithm 1 (+ N:M rule of Sec. 4) and Algorithm 3 --------------------------------
+ * Workspace for obc_prune_rows / obc_quant_rows on R rows of width d. */
+int obc_rows_workspace_bytes(int R, int d, int strategy, size_t *bytes);
+
+/* Prune every row of W independently with Algorithm 1, each on a private copy of Hinv.
+ *   W        R x d   weights (input)
+ *   Hinv     d x d   symmetric inverse Hessian shared by all rows (input)
+ *   k_steps  greedy steps per row, 0 <= k_steps <= d (N:M: <= d (M-N)/M)
+ *   nm_n, nm_m   N:M pattern: a weight is eligible while its block of nm_m consecutive
+ *            indices has fewer than nm_m - nm_n pruned weights; nm_m == 0: unstructured
+ *   stop_counts  nullable, R: row i stops after min(k_steps, stop_counts[i]) steps (replay of
+ *            the counts chosen by obc_global_select); entries of order/loss beyond are untouched
+ *   order    R x k_steps int32 out: index pruned at each step
+ *   loss     R x k_steps fp32 out: loss change w_p^2 / (2 [H^-1]_pp) of each step
+ *   W_out    R x d out: the row after its last step (pruned weights exactly 0)
+ *   trace    nullable, R x k_steps x d out: the row after every step (the "pruning trace" of
+ *            Sec. 4 Step 2, kept in HBM here)
+ * Ties in the argmin go to the lowest index. */
+int obc_prune_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d, int k_steps,
+                   int nm_n, int nm_m, const int32_t *stop_counts, int32_t *order, float *loss,
+                   float *W_out, float *trace, int strategy, void *ws, size_t ws_bytes);
+
+/* Quantize every row with Algorithm 3 on the caller's per-row uniform grid
+ *   q(w) = offset[i] + delta[i] * clamp(rne((w - offset[i]) / delta[i]), 0, maxq).
+ *   live     nullable, R x d: 0 marks an already pruned weight; those are first removed from the
+ *            row's inverse (Lemma 1, no weight change) so that OBQ runs on the dense sub-problem
+ *            of the survivors; they keep weight 0 and get code -1.
+ *   order, loss   R x d: entries [0, #live_i) are written for row i
+ *   codes    R x d int32 out: grid code of each weight at the moment it was chosen
+ *   W_out    R x d out: dequantized weights offset + delta * code */
+int obc_quant_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d,
+                   const float *delta, const float *offset, int maxq, const uint8_t *live,
+                   int32_t *order, float *loss, int32_t *codes, float *W_out, int strategy,
+                   void *ws, size_t ws_bytes);
+
+/* Per-row asymmetric min-max grid over the live weights: offset = min, delta = (max - min)/maxq
+ * (delta = 1 when max == min or no weight is live).  live nullable = all live. */
+int obc_minmax_grid(obc_ctx *ctx, const float *W, const uint8_t *live, int R, int d, int maxq,
+                    float *delta, float *offset);
+
+/* ---- Appendix Algorithm 2: the global step ---------------------------------------------
+ * From the per-row loss traces (loss, order: R x d as written by obc_prune_rows with
+ * k_steps == d) find how many weights each row gives up when k weights are pruned from the
+ * layer: k times, the row whose next loss change is smallest advances (lowest row on ties).
+ *   counts   R int32 out;  mask  R x d uint8 out, 1 = pruned. */
+int obc_global_select_workspace_bytes(int R, int d, size_t *bytes);
+int obc_global_select(obc_ctx *ctx, const float *loss, const int32_t *order, int R, int d,
+                      int64_t k, int32_t *counts, uint8_t *mask, void *ws, size_t ws_bytes);
+
+/* ---- Sec. 4 Step 2: weights of the chosen mask from the pruning trace -------------------
+ * W_out[i] = trace[i][counts[i]-1] (the row after counts[i] steps), or W[i] when counts[i] == 0.
+ * trace is R x k_steps x d with k_steps >= max counts. */
+int obc_gather_trace(obc_ctx *ctx, const float *W, const float *trace, const int32_t *counts,
+                     int R, int d, int k_steps, float *W_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OBC_H */

@@ -1,0 +1,54 @@
+// Shared host-side pieces of libobc: the context object, error plumbing, small helpers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "../../include/obc.h"
+
+struct obc_ctx {
+    hipStream_t stream;
+    int device;
+    int *d_status;      // device error latch: 0, or the first OBC_ERR_* a kernel saw
+    char err[512];
+};
+
+static inline int obc_fail(obc_ctx *ctx, int code, const char *fmt, ...)
+{
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+#define OBC_HIP(ctx, call)                                                              \
+    do {                                                                                \
+        hipError_t e__ = (call);                                                        \
+        if (e__ != hipSuccess)                                                          \
+            return obc_fail((ctx), OBC_ERR_HIP, "%s failed: %s (%s:%d)", #call,        \
+                            hipGetErrorString(e__), __FILE__, __LINE__);                \
+    } while (0)
+
+#define OBC_LAUNCH_CHECK(ctx, name)                                                     \
+    do {                                                                                \
+        hipError_t e__ = hipGetLastError();                                             \
+        if (e__ != hipSuccess)                                                          \
+            return obc_fail((ctx), OBC_ERR_HIP, "launch of %s failed: %s", (name),      \
+                            hipGetErrorString(e__));                                    \
+    } while (0)
+
+__host__ __device__ static inline size_t obc_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Latch the first error seen by any kernel (device side).
+__device__ static inline void obc_latch(int *status, int code)
+{
+    atomicCAS(status, 0, code);
+}

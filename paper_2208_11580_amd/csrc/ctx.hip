@@ -1,0 +1,58 @@
+// Context life cycle and the device error latch.
+#include "common.h"
+
+extern "C" {
+
+const char *obc_version(void) { return "libobc 0.1 (gfx950)"; }
+
+int obc_create(obc_ctx **out, void *hip_stream)
+{
+    if (!out) return OBC_ERR_BAD_ARG;
+    *out = nullptr;
+    obc_ctx *ctx = new (std::nothrow) obc_ctx;
+    if (!ctx) return OBC_ERR_BAD_ARG;
+    ctx->stream = (hipStream_t)hip_stream;
+    ctx->d_status = nullptr;
+    ctx->err[0] = 0;
+    ctx->device = 0;
+    hipError_t e = hipGetDevice(&ctx->device);
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->d_status, 256);
+    if (e == hipSuccess) e = hipMemsetAsync(ctx->d_status, 0, 256, ctx->stream);
+    if (e != hipSuccess) {
+        if (ctx->d_status) (void)hipFree(ctx->d_status);
+        delete ctx;
+        return OBC_ERR_HIP;
+    }
+    *out = ctx;
+    return OBC_OK;
+}
+
+int obc_destroy(obc_ctx *ctx)
+{
+    if (!ctx) return OBC_ERR_BAD_ARG;
+    (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->d_status) (void)hipFree(ctx->d_status);
+    delete ctx;
+    return OBC_OK;
+}
+
+const char *obc_last_error(const obc_ctx *ctx) { return ctx ? ctx->err : "null context"; }
+
+int obc_check(obc_ctx *ctx)
+{
+    if (!ctx) return OBC_ERR_BAD_ARG;
+    int h = 0;
+    OBC_HIP(ctx, hipMemcpyAsync(&h, ctx->d_status, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+    OBC_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (h != 0) {
+        OBC_HIP(ctx, hipMemsetAsync(ctx->d_status, 0, sizeof(int), ctx->stream));
+        OBC_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        return obc_fail(ctx, h, "a kernel reported error %d (%s)", h,
+                        h == OBC_ERR_NUMERIC   ? "non-positive or non-finite pivot in a row solver"
+                        : h == OBC_ERR_NOT_SPD ? "matrix is not positive definite"
+                                               : "unknown");
+    }
+    return OBC_OK;
+}
+
+}  // extern "C"

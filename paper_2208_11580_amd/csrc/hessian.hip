@@ -1,0 +1,224 @@
+// obc_hessian: H = 2 X X^T (+ dampening), Sec. 4 of arxiv 2208.11580.
+//
+// A dense symmetric rank-N contraction, so it runs on the fp32 matrix cores:
+// v_mfma_f32_32x32x2_f32, 128x128 output tiles per 256-thread workgroup (four waves, each
+// 64x64 = 2x2 MFMA tiles), X staged through LDS k-major so that the MFMA operand reads are
+// bank-conflict free.  Only tiles on or above the block diagonal are computed; the
+// contraction length N is cut into S slices so that small d still fills 256 CUs.  Slices go
+// to a workspace and are summed in a fixed order by a second kernel, which also mirrors the
+// upper tiles into the lower triangle (H comes out exactly symmetric) -- no float atomics,
+// results are deterministic.
+#include "common.h"
+
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128;       // tile edge
+constexpr int BK = 16;        // k-slab per LDS stage
+constexpr int LDT = BM + 4;   // padded LDS row
+
+__host__ __device__ inline int tiles_of(int d) { return (d + BM - 1) / BM; }
+
+// How many slices of the sample axis, and how long each is (multiple of BK).
+inline void split_plan(int d, int64_t N, int *S, int64_t *kchunk)
+{
+    int nt = tiles_of(d);
+    int64_t ntri = (int64_t)nt * (nt + 1) / 2;
+    int64_t s = (1024 + ntri - 1) / ntri;
+    int64_t smax = (N + 2047) / 2048;
+    if (s > smax) s = smax;
+    if (s < 1) s = 1;
+    int64_t kc = (N + s - 1) / s;
+    kc = (kc + BK - 1) / BK * BK;
+    if (kc < BK) kc = BK;
+    s = (N + kc - 1) / kc;
+    if (s < 1) s = 1;
+    *S = (int)s;
+    *kchunk = kc;
+}
+
+__global__ __launch_bounds__(256) void syrk_partial_kernel(const float *__restrict__ X, int d,
+                                                           int64_t N, int64_t ldx, int64_t kchunk,
+                                                           float *__restrict__ partial, int vec_ok)
+{
+    __shared__ float As[BK][LDT];
+    __shared__ float Bs[BK][LDT];
+
+    // upper-triangular tile enumeration: blockIdx.x -> (ti <= tj)
+    const int nt = tiles_of(d);
+    int t = blockIdx.x, ti = 0, rowlen = nt;
+    while (t >= rowlen) { t -= rowlen; ++ti; --rowlen; }
+    const int tj = ti + t;
+    const bool on_diag = (ti == tj);
+
+    const int64_t kbeg = (int64_t)blockIdx.y * kchunk;
+    const int64_t kend = (kbeg + kchunk < N) ? kbeg + kchunk : N;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    // loader: a 128 x 16 slab is 512 float4; thread takes quads tid and tid + 256
+    float4 ra[2], rb[2];
+    auto fetch = [&](int tile, int64_t k0, float4(&r)[2]) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            int f = tid + h * 256;
+            int row = tile * BM + (f >> 2);
+            int64_t k = k0 + (f & 3) * 4;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < d) {
+                const float *src = X + (int64_t)row * ldx + k;
+                if (vec_ok && k + 3 < kend) {
+                    v = *reinterpret_cast<const float4 *>(src);
+                } else {
+                    if (k + 0 < kend) v.x = src[0];
+                    if (k + 1 < kend) v.y = src[1];
+                    if (k + 2 < kend) v.z = src[2];
+                    if (k + 3 < kend) v.w = src[3];
+                }
+            }
+            r[h] = v;
+        }
+    };
+    auto stash = [&](float(&T)[BK][LDT], const float4(&r)[2]) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            int f = tid + h * 256;
+            int row = f >> 2, kq = (f & 3) * 4;
+            T[kq + 0][row] = r[h].x;
+            T[kq + 1][row] = r[h].y;
+            T[kq + 2][row] = r[h].z;
+            T[kq + 3][row] = r[h].w;
+        }
+    };
+
+    if (kbeg < kend) {
+        fetch(ti, kbeg, ra);
+        if (!on_diag) fetch(tj, kbeg, rb);
+    }
+    for (int64_t k0 = kbeg; k0 < kend; k0 += BK) {
+        stash(As, ra);
+        if (!on_diag) stash(Bs, rb);
+        __syncthreads();
+        if (k0 + BK < kend) {
+            fetch(ti, k0 + BK, ra);
+            if (!on_diag) fetch(tj, k0 + BK, rb);
+        }
+        const float(*Bt)[LDT] = on_diag ? As : Bs;
+        const int kl = lane >> 5, il = lane & 31;
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2) {
+            float a0 = As[kk + kl][wm * 64 + il];
+            float a1 = As[kk + kl][wm * 64 + 32 + il];
+            float b0 = Bt[kk + kl][wn * 64 + il];
+            float b1 = Bt[kk + kl][wn * 64 + 32 + il];
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    // accumulator layout of the 32x32 MFMA: lane holds column (lane % 32) and, for register v,
+    // row 8 * (v / 4) + 4 * (lane / 32) + v % 4
+    float *out = partial + (int64_t)blockIdx.y * d * d;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int i = ti * BM + wm * 64 + a * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                int j = tj * BM + wn * 64 + b * 32 + (lane & 31);
+                if (i < d && j < d) out[(int64_t)i * d + j] = acc[a][b][v];
+            }
+}
+
+// H[i][j] (+)= 2 * sum_s partial[s][min-tile-order(i, j)], slices added in index order.
+__global__ __launch_bounds__(256) void syrk_reduce_kernel(const float *__restrict__ partial, int S,
+                                                          int d, int accumulate,
+                                                          float *__restrict__ H)
+{
+    int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= (int64_t)d * d) return;
+    int i = (int)(e / d), j = (int)(e % d);
+    int64_t src = (i / BM <= j / BM) ? (int64_t)i * d + j : (int64_t)j * d + i;
+    float s = 0.f;
+    for (int k = 0; k < S; ++k) s += partial[(int64_t)k * d * d + src];
+    s *= 2.f;
+    H[e] = accumulate ? H[e] + s : s;
+}
+
+// diag(H) += damp_rel * mean(diag(H)); one workgroup, fixed-order tree sum in fp64.
+__global__ __launch_bounds__(1024) void dampen_kernel(float *__restrict__ H, int d, float damp_rel)
+{
+    __shared__ double red[1024];
+    double s = 0.0;
+    for (int j = threadIdx.x; j < d; j += blockDim.x) s += (double)H[(int64_t)j * d + j];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = blockDim.x / 2; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    float lam = (float)((double)damp_rel * red[0] / (double)d);
+    for (int j = threadIdx.x; j < d; j += blockDim.x) H[(int64_t)j * d + j] += lam;
+}
+
+}  // namespace
+
+extern "C" {
+
+int obc_hessian_workspace_bytes(int d, int64_t N, size_t *bytes)
+{
+    if (!bytes || d <= 0 || N < 0) return OBC_ERR_BAD_ARG;
+    int S;
+    int64_t kc;
+    split_plan(d, N > 0 ? N : 1, &S, &kc);
+    *bytes = obc_align_up((size_t)S * d * d * sizeof(float), 256);
+    return OBC_OK;
+}
+
+int obc_hessian(obc_ctx *ctx, const float *X, int d, int64_t N, int64_t ldx, float damp_rel,
+                int accumulate, float *H, void *ws, size_t ws_bytes)
+{
+    if (!ctx) return OBC_ERR_BAD_ARG;
+    if (!X || !H) return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_hessian: null X or H");
+    if (d <= 0 || N <= 0) return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_hessian: d and N must be positive");
+    if (ldx < N) return obc_fail(ctx, OBC_ERR_BAD_SHAPE, "obc_hessian: ldx (%lld) < N (%lld)", (long long)ldx, (long long)N);
+    size_t need;
+    obc_hessian_workspace_bytes(d, N, &need);
+    if (!ws || ws_bytes < need)
+        return obc_fail(ctx, OBC_ERR_WORKSPACE, "obc_hessian: workspace of %zu bytes needed, %zu given", need, ws_bytes);
+
+    int S;
+    int64_t kchunk;
+    split_plan(d, N, &S, &kchunk);
+    const int nt = tiles_of(d);
+    const int ntri = nt * (nt + 1) / 2;
+    const int vec_ok = (ldx % 4 == 0) && (((uintptr_t)X & 15) == 0);
+    float *partial = (float *)ws;
+
+    syrk_partial_kernel<<<dim3(ntri, S), 256, 0, ctx->stream>>>(X, d, N, ldx, kchunk, partial, vec_ok);
+    OBC_LAUNCH_CHECK(ctx, "syrk_partial_kernel");
+    const int64_t n = (int64_t)d * d;
+    syrk_reduce_kernel<<<(unsigned)((n + 255) / 256), 256, 0, ctx->stream>>>(partial, S, d, accumulate, H);
+    OBC_LAUNCH_CHECK(ctx, "syrk_reduce_kernel");
+    if (damp_rel >= 0.f) {
+        dampen_kernel<<<1, 1024, 0, ctx->stream>>>(H, d, damp_rel);
+        OBC_LAUNCH_CHECK(ctx, "dampen_kernel");
+    }
+    return OBC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,129 @@
+"""GPU-vs-oracle comparison protocol for the row solvers.
+
+The oracle is fed exactly what the GPU solver was fed (the fp32 inverse Hessian, weights and grid,
+up-cast to fp64).  Tolerances (stated by the build's target):
+
+* order / masks: identical wherever the oracle's candidate gap exceeds 1e-6 relative.  At a
+  mismatch the GPU's pick must score within 1e-6 relative of the oracle's minimum in the oracle's
+  own state; the oracle then follows the GPU's order (swapping two near-tied picks gives the same
+  state two steps later), so one benign swap does not cascade.
+* surviving weights: ||w_gpu - w_orc||_2 <= 1e-4 ||w_orc||_2 per row
+* loss changes: the row's accumulated loss within 1e-3 relative
+* quantized codes: exact, except where the oracle's pre-rounding value lies within 1e-4 of a
+  half-integer at the moment of choice (fp32 and fp64 cannot agree there)
+"""
+import numpy as np
+
+ORDER_GAP = 1e-6
+W_RTOL = 1e-4
+LOSS_RTOL = 1e-3
+HALF_EPS = 1e-4
+
+
+class RowParity:
+    def __init__(self):
+        self.rows = 0
+        self.steps = 0
+        self.order_mismatch_rows = 0
+        self.near_ties = 0
+        self.code_exempt = 0
+        self.max_w_err = 0.0
+        self.max_loss_err = 0.0
+
+    def __repr__(self):
+        return ("RowParity(rows=%d steps=%d rows_with_swaps=%d near_ties=%d code_exempt=%d "
+                "max_w_err=%.2e max_loss_err=%.2e)" % (self.rows, self.steps, self.order_mismatch_rows,
+                                                      self.near_ties, self.code_exempt, self.max_w_err,
+                                                      self.max_loss_err))
+
+
+def check_row(orc, stats, mode, Hinv32, w32, g_order, g_loss, g_w, k_steps, nm=(0, 0), grid=None,
+              g_codes=None, live=None, g_trace=None):
+    """Compare one GPU row with the oracle.  All g_* are numpy arrays of the GPU outputs."""
+    A = np.asarray(Hinv32, np.float64)
+    w = np.asarray(w32, np.float64)
+    d = w.shape[0]
+    S = np.arange(d) if live is None else np.flatnonzero(np.asarray(live) != 0)
+    sub = live is not None and S.size < d
+    if sub:
+        # survivors only: the oracle works on the dense sub-problem, whose inverse it forms by
+        # direct inversion of the sub-Hessian; here the sub-Hessian is inv(A)[S, S]
+        H = np.linalg.inv(A)
+        H = 0.5 * (H + H.T)
+        A = orc.invert(H[np.ix_(S, S)])
+        w = w[S]
+        remap = -np.ones(d, np.int64)
+        remap[S] = np.arange(S.size)
+        g_order_l = remap[np.asarray(g_order[:k_steps], np.int64)]
+        assert np.all(g_order_l >= 0), "GPU picked a dead index"
+    else:
+        g_order_l = np.asarray(g_order[:k_steps], np.int64)
+    assert len(set(g_order_l.tolist())) == k_steps, "GPU order repeats an index"
+
+    def run(forced):
+        if mode == "prune":
+            return orc.prune_row(A, w, k_steps=k_steps, nm=nm, forced=forced, want_trace=g_trace is not None)
+        return orc.quant_row(A, w, grid, k_steps=k_steps, forced=forced)
+
+    r = run(None)
+    stats.rows += 1
+    stats.steps += k_steps
+    if not np.array_equal(r.order, g_order_l):
+        stats.order_mismatch_rows += 1
+        r = run(g_order_l.astype(np.int32))
+        scale = float(np.max(r.min_score)) if k_steps else 0.0
+        gap = r.pick_score - r.min_score
+        bad = gap > ORDER_GAP * r.min_score + 1e-12 * scale
+        assert not np.any(bad), "GPU pick beyond the 1e-6 gap at steps %s (gaps %s)" % (
+            np.flatnonzero(bad)[:5], (gap / np.maximum(r.min_score, 1e-300))[bad][:5])
+        stats.near_ties += int(np.count_nonzero(gap > 0))
+    # weights
+    gw = np.asarray(g_w, np.float64)
+    gw_l = gw[S] if sub else gw
+    if sub:
+        dead = np.setdiff1d(np.arange(d), S)
+        assert np.all(gw[dead] == 0.0)
+    ref = r.w
+    nrm = np.linalg.norm(ref)
+    err = np.linalg.norm(gw_l - ref)
+    if nrm > 0:
+        stats.max_w_err = max(stats.max_w_err, err / nrm)
+        assert err <= W_RTOL * nrm, "weights differ: rel %.3e" % (err / nrm)
+    else:
+        assert err == 0.0
+    chosen = g_order_l
+    if mode == "prune":
+        assert np.all(gw_l[chosen] == 0.0), "pruned weights must be exactly zero"
+    # losses
+    gl = np.asarray(g_loss[:k_steps], np.float64)
+    tot = r.loss.sum()
+    if tot > 0:
+        e = abs(gl.sum() - tot) / tot
+        stats.max_loss_err = max(stats.max_loss_err, e)
+        assert e <= LOSS_RTOL, "accumulated loss differs: rel %.3e" % e
+    assert np.allclose(gl, r.loss, rtol=5e-3, atol=1e-6 * (np.max(r.loss) if k_steps else 0.0))
+    # codes
+    if mode == "quant" and g_codes is not None:
+        gc = np.asarray(g_codes)
+        gc_l = gc[S] if sub else gc
+        if sub:
+            assert np.all(gc[np.setdiff1d(np.arange(d), S)] == -1)
+        diff = np.flatnonzero(gc_l != r.codes)
+        if diff.size:
+            # the step at which each differing index was chosen
+            step_of = np.empty(len(w), np.int64)
+            step_of[r.order] = np.arange(k_steps)
+            frac = np.abs(r.pre_round[step_of[diff]] - np.floor(r.pre_round[step_of[diff]]) - 0.5)
+            assert np.all(frac < HALF_EPS), "codes differ away from a rounding boundary at %s" % diff[:5]
+            stats.code_exempt += diff.size
+        delta, offset, maxq = grid
+        assert gc_l.min() >= 0 and gc_l.max() <= maxq
+        deq = np.float32(offset) + np.float32(delta) * gc_l.astype(np.float32)
+        assert np.array_equal(gw_l.astype(np.float32), deq.astype(np.float32))
+    if g_trace is not None and mode == "prune":
+        gt = np.asarray(g_trace[:k_steps], np.float64)
+        num = np.linalg.norm(gt - r.trace, axis=1)
+        den = np.linalg.norm(r.trace, axis=1)
+        ok = num <= W_RTOL * den + 1e-30
+        assert np.all(ok), "trace differs at steps %s" % np.flatnonzero(~ok)[:5]
+    return r

@@ -1,0 +1,65 @@
+"""The C-ABI library loads on a machine without a GPU and exports every symbol include/obc.h declares."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "obc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(obc_[a-z0-9_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2208_11580_amd import binding
+
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2208_11580_amd import build
+
+        build.build_lib()
+    return binding.load_library()
+
+
+def test_header_declares_the_boundary():
+    syms = _declared_symbols()
+    for name in ("obc_hessian", "obc_invert", "obc_prune_rows", "obc_quant_rows", "obc_global_select"):
+        assert name in syms
+
+
+def test_library_exports_every_declared_symbol(lib):
+    from paper_2208_11580_amd import binding
+
+    syms = _declared_symbols()
+    assert sorted(binding.EXPORTS) == syms
+    for name in syms:
+        assert hasattr(lib, name), name
+
+
+def test_host_only_calls(lib):
+    assert b"gfx950" in lib.obc_version()
+    n = ctypes.c_size_t()
+    assert lib.obc_rows_workspace_bytes(256, 2304, 1, ctypes.byref(n)) == 0
+    assert n.value >= 256 * 2304 * 2304 * 4
+    assert lib.obc_rows_workspace_bytes(16, 32, 0, ctypes.byref(n)) == 0 and n.value <= 4096
+    assert lib.obc_rows_workspace_bytes(-1, 32, 0, ctypes.byref(n)) == -1
+    assert lib.obc_rows_workspace_bytes(1, 32, 7, ctypes.byref(n)) == -1
+    assert lib.obc_invert_workspace_bytes(0, ctypes.byref(n)) == -1
+    assert lib.obc_invert_workspace_bytes(100, ctypes.byref(n)) == 0 and n.value >= 2 * 100 * 100 * 8
+    assert lib.obc_hessian_workspace_bytes(576, 50000, ctypes.byref(n)) == 0 and n.value >= 576 * 576 * 4
+    assert lib.obc_global_select_workspace_bytes(64, 576, ctypes.byref(n)) == 0 and n.value >= 64 * 576 * 4
+    assert lib.obc_last_error(None) == b"null context"
+
+
+def test_no_oracle_in_product_path():
+    """The package never imports the oracle (the oracle is test infrastructure)."""
+    pkg = os.path.join(ROOT, "paper_2208_11580_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), (dirpath, f)
