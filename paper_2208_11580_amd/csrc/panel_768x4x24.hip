@@ -1,0 +1,6 @@
+// Panel kernel variant: 768 threads, 4 owned indices per thread, blocks of 24 steps.
+#include "panel_impl.h"
+
+namespace obc_blocked {
+OBC_DEFINE_PANEL(768, 4, 24)
+}

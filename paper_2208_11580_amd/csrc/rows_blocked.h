@@ -1,0 +1,64 @@
+// Declarations shared by the blocked row solver's translation units: workspace layout, kernel
+// argument blocks, and the per-variant panel launchers (one translation unit per variant so that
+// the heavily unrolled panel kernels compile in parallel).
+#pragma once
+
+#include "rows_common.h"
+
+namespace obc_blocked {
+
+using namespace obc_rows;
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BMAX = 64;       // largest block; leading dimension of the per-row U / pivot arrays
+constexpr int FT = 128;        // flush tile edge
+constexpr int FLD = FT + 4;    // padded LDS row of the flush operand tiles
+
+struct BlockedWs {
+    float *Abuf[2];     // R x d x d each
+    float *U;           // R x BMAX x d
+    float *invd;        // R x BMAX
+    int *piv;           // R x BMAX  (compact index of each pivot of the current block)
+    int *map;           // R x d     (new compact index -> old compact index)
+    double *w;          // R x d     (compact)
+    double *diag;       // R x d
+    int *orig;          // R x d     compact -> original index; ~index for an already-pruned weight
+    int *m;             // R   live size
+    int *done;          // R   steps done (including up-front eliminations)
+    int *total;         // R   steps to do
+    int *ndead;         // R   up-front eliminations
+    int *nb;            // R   steps done in the last panel
+    uint8_t *blk;       // R x d  N:M counters (d / M used)
+};
+
+
+struct PanelArgs {
+    const float *A_cur;      // matrix buffer the rows are read from
+    size_t a_row_stride;     // elements between two rows' matrices (0: all rows share H^-1)
+    int ld;                  // leading dimension of A_cur
+    int d;                   // original width (stride of the per-row state arrays)
+    int nm_n, nm_m;
+    const float *delta, *offset;
+    int maxq;
+    BlockedWs ws;
+    int32_t *order;
+    float *loss;
+    int32_t *codes;
+    float *W_out;
+    float *trace;
+    int out_ld;
+    int *status;
+};
+
+// launchers defined in panel_<T>x<EPT>x<B>.hip
+#define OBC_DECLARE_PANEL(T, EPT, B) \
+    void launch_panel_##T##_##EPT##_##B(int mode, int R, size_t lds, hipStream_t st, const PanelArgs &a)
+OBC_DECLARE_PANEL(256, 1, 64);
+OBC_DECLARE_PANEL(1024, 1, 64);
+OBC_DECLARE_PANEL(1024, 2, 32);
+OBC_DECLARE_PANEL(768, 3, 32);
+OBC_DECLARE_PANEL(768, 4, 24);
+OBC_DECLARE_PANEL(768, 6, 16);
+
+}  // namespace obc_blocked

@@ -1,22 +1,322 @@
-// Row solver, blocked strategy (placeholder: forwards to the rank-1 solver until the blocked
-// kernels land).
-#include "rows_common.h"
+// Row solver, blocked strategy: the greedy loops of Algorithm 1 / Algorithm 3 (arxiv 2208.11580)
+// with the Lemma-1 eliminations applied to the row's private inverse in blocks of B steps.
+//
+// What a greedy step needs is small: the current diagonal of A, the current weights, and the
+// current row p of A.  The first two are O(d) to maintain.  Row p can be formed on demand from
+// the matrix as of the last block boundary, A0, and the eliminations done since:
+//
+//     A[p,:] = A0[p,:] - sum_r (u_r[p] / a_r) u_r        u_r = row p_r of A when p_r was chosen,
+//                                                        a_r = its diagonal entry
+//
+// so inside a block nothing of size d^2 moves.  Every B steps the deferred eliminations are
+// applied at once,  A0 <- A0 - U diag(1/a) U^T,  a dense rank-B contraction that runs on the fp32
+// matrix cores and touches A once per B steps instead of once per step.  The result is the same
+// sequence of exact OBS steps; only the order of fp32 roundings inside A differs from the
+// rank-1 strategy.
+//
+// Two kernels alternate on the stream (host loop, no host synchronisation):
+//
+//   panel_kernel  one workgroup per row, B greedy steps.  Thread t owns the compact indices
+//                 t, t+T, ...: their weights and diagonal (fp64) and the B vectors u_r live in its
+//                 registers.  Per step: fp64 score + workgroup argmin (barrier 1), the owner of p
+//                 publishes w_p, a_p and the coefficients u_r[p]/a_r while every thread fetches its
+//                 part of A0[p,:] (barrier 2), then the row is corrected, w / diag are updated and
+//                 u_s is kept (registers) and stored (HBM, for the flush).
+//   flush_kernel  A0_new = compact(A0 - U diag(1/a) U^T): 128x128 tiles on v_mfma_f32_32x32x2_f32,
+//                 one workgroup per 128-row strip of one row's matrix.  The eliminated rows and
+//                 columns are dropped while writing (out of place, two buffers), so the matrix
+//                 shrinks with the live set and later blocks cost (m/d)^2 of the first.
+//
+// The first block reads the shared H^-1 directly, so no per-row copy of it is ever made.
+// Already-pruned weights (quantization of survivors) enter as candidates with score -1: they are
+// eliminated first, in index order, with no weight change and nothing recorded.
+#include "rows_blocked.h"
+
+namespace {
+
+using namespace obc_blocked;
+
+size_t carve(BlockedWs *ws, void *base, int R, int d)
+{
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off += obc_align_up(bytes, 256);
+        return base ? (char *)base + o : (char *)nullptr;
+    };
+    size_t mat = (size_t)R * d * d * sizeof(float);
+    char *p0 = take(mat), *p1 = take(mat);
+    char *pu = take((size_t)R * BMAX * d * sizeof(float));
+    char *pi = take((size_t)R * BMAX * sizeof(float));
+    char *pp = take((size_t)R * BMAX * sizeof(int));
+    char *pm = take((size_t)R * d * sizeof(int));
+    char *pw = take((size_t)R * d * sizeof(double));
+    char *pd = take((size_t)R * d * sizeof(double));
+    char *po = take((size_t)R * d * sizeof(int));
+    char *s0 = take((size_t)R * sizeof(int)), *s1 = take((size_t)R * sizeof(int));
+    char *s2 = take((size_t)R * sizeof(int)), *s3 = take((size_t)R * sizeof(int));
+    char *s4 = take((size_t)R * sizeof(int));
+    char *pb = take((size_t)R * d);
+    if (ws) {
+        ws->Abuf[0] = (float *)p0; ws->Abuf[1] = (float *)p1; ws->U = (float *)pu;
+        ws->invd = (float *)pi; ws->piv = (int *)pp; ws->map = (int *)pm; ws->w = (double *)pw;
+        ws->diag = (double *)pd; ws->orig = (int *)po; ws->m = (int *)s0; ws->done = (int *)s1;
+        ws->total = (int *)s2; ws->ndead = (int *)s3; ws->nb = (int *)s4; ws->blk = (uint8_t *)pb;
+    }
+    return off;
+}
+
+// ------------------------------------------------------------------------------------------ init
+struct InitArgs {
+    const float *W, *Hinv;
+    const uint8_t *live_in;
+    const int32_t *stop_counts;
+    int d, k_steps, mode;
+    BlockedWs ws;
+    int32_t *codes;
+    float *W_out;
+};
+
+__global__ __launch_bounds__(256) void blocked_init_kernel(InitArgs a)
+{
+    __shared__ int cnt;
+    const int row = blockIdx.x, tid = threadIdx.x, d = a.d;
+    if (tid == 0) cnt = 0;
+    __syncthreads();
+    int dead_local = 0;
+    for (int j = tid; j < d; j += 256) {
+        bool alive = (a.mode == MODE_QUANT && a.live_in) ? a.live_in[(size_t)row * d + j] != 0 : true;
+        a.ws.w[(size_t)row * d + j] = alive ? (double)a.W[(size_t)row * d + j] : 0.0;
+        a.ws.diag[(size_t)row * d + j] = (double)a.Hinv[(size_t)j * d + j];
+        a.ws.orig[(size_t)row * d + j] = alive ? j : ~j;
+        a.ws.blk[(size_t)row * d + j] = 0;
+        a.W_out[(size_t)row * d + j] = 0.f;
+        if (a.mode == MODE_QUANT) a.codes[(size_t)row * d + j] = -1;
+        dead_local += alive ? 0 : 1;
+    }
+    atomicAdd(&cnt, dead_local);
+    __syncthreads();
+    if (tid == 0) {
+        int total = a.k_steps;
+        if (a.mode == MODE_QUANT) total = d;   // eliminations of the dead + one step per survivor
+        if (a.stop_counts) {
+            int sc = a.stop_counts[row];
+            sc = sc < 0 ? 0 : sc;
+            total = sc < total ? sc : total;
+        }
+        a.ws.m[row] = d;
+        a.ws.done[row] = 0;
+        a.ws.total[row] = total;
+        a.ws.ndead[row] = cnt;
+        a.ws.nb[row] = 0;
+    }
+}
+
+__global__ __launch_bounds__(256) void fill_f32_kernel(float *p, size_t n, float v)
+{
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n; e += (size_t)gridDim.x * 256) p[e] = v;
+}
+
+// ----------------------------------------------------------------------------------------- flush
+struct FlushArgs {
+    const float *A_old;
+    size_t old_row_stride;   // 0 when every row still reads the shared H^-1
+    int ld_old;
+    float *A_new;
+    size_t new_row_stride;
+    int ld_new;
+    int d, R, strips;
+    BlockedWs ws;
+};
+
+__global__ __launch_bounds__(256) void flush_kernel(FlushArgs a)
+{
+    __shared__ float Fs[BMAX][FLD];
+    __shared__ float Us[BMAX][FLD];
+
+    // workgroups are dealt round-robin to the 8 XCDs: keep all strips of one row on one XCD so
+    // that its U panel and index map stay in that XCD's L2
+    const int L = blockIdx.x;
+    const int row = (L / (8 * a.strips)) * 8 + (L % 8);
+    const int strip = (L / 8) % a.strips;
+    if (row >= a.R) return;
+    const int nb = a.ws.nb[row];
+    if (nb == 0 || a.ws.done[row] >= a.ws.total[row]) return;
+    const int mn = a.ws.m[row];             // live size after the block (new compact space)
+    const int i0 = strip * FT;
+    if (i0 >= mn) return;
+
+    const int d = a.d;
+    const float *Aold = a.A_old + (size_t)row * a.old_row_stride;
+    float *Anew = a.A_new + (size_t)row * a.new_row_stride;
+    const int *map = a.ws.map + (size_t)row * d;
+    const float *U = a.ws.U + (size_t)row * BMAX * d;
+    const float *invd = a.ws.invd + (size_t)row * BMAX;
+    const int ldo = a.ld_old, ldn = a.ld_new;
+    const int nbp = (nb + 1) & ~1;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // F tile: F[k][i] = -u_k[i] / a_k for the strip's rows (old compact positions via the map)
+    for (int idx = tid; idx < nbp * FT; idx += 256) {
+        int k = idx / FT, i = idx % FT;
+        int ii = i0 + i;
+        float v = 0.f;
+        if (k < nb && ii < mn) v = -__fmul_rn(U[(size_t)k * d + map[ii]], invd[k]);
+        Fs[k][i] = v;
+    }
+    // element offsets of the 32 matrix rows this lane holds in its accumulators
+    int roff[2][16];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            int ii = i0 + wm * 64 + mt * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            roff[mt][v] = (ii < mn) ? map[ii] * ldo : -1;
+        }
+
+    for (int j0 = 0; j0 < mn; j0 += FT) {
+        __syncthreads();
+        for (int idx = tid; idx < nbp * FT; idx += 256) {
+            int k = idx / FT, j = idx % FT;
+            int jj = j0 + j;
+            float v = 0.f;
+            if (k < nb && jj < mn) v = U[(size_t)k * d + map[jj]];
+            Us[k][j] = v;
+        }
+        floatx16 acc[2][2];
+        int jcol[2], jold[2];
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            jcol[nt] = j0 + wn * 64 + nt * 32 + (lane & 31);
+            jold[nt] = (jcol[nt] < mn) ? map[jcol[nt]] : -1;
+        }
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    acc[mt][nt][v] = (roff[mt][v] >= 0 && jold[nt] >= 0) ? Aold[(size_t)roff[mt][v] + jold[nt]] : 0.f;
+        __syncthreads();
+        const int kl = lane >> 5, il = lane & 31;
+        for (int kk = 0; kk < nbp; kk += 2) {
+            float a0 = Fs[kk + kl][wm * 64 + il];
+            float a1 = Fs[kk + kl][wm * 64 + 32 + il];
+            float b0 = Us[kk + kl][wn * 64 + il];
+            float b1 = Us[kk + kl][wn * 64 + 32 + il];
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    int ii = i0 + wm * 64 + mt * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                    if (ii < mn && jcol[nt] < mn) Anew[(size_t)ii * ldn + jcol[nt]] = acc[mt][nt][v];
+                }
+    }
+}
+
+// ------------------------------------------------------------------------------------- host side
+struct Variant {
+    int cap;   // largest live size it handles (T * EPT)
+    int B;
+    void (*launch)(int, int, size_t, hipStream_t, const PanelArgs &);
+};
+
+#define OBC_VARIANT(T, EPT, B) { (T) * (EPT), (B), launch_panel_##T##_##EPT##_##B }
+
+const Variant kVariants[] = {
+    OBC_VARIANT(256, 1, 64), OBC_VARIANT(1024, 1, 64), OBC_VARIANT(1024, 2, 32),
+    OBC_VARIANT(768, 3, 32), OBC_VARIANT(768, 4, 24),  OBC_VARIANT(768, 6, 16),
+};
+constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+
+const Variant *pick_variant(int m)
+{
+    for (int i = 0; i < kNumVariants; ++i)
+        if (m <= kVariants[i].cap) return &kVariants[i];
+    return nullptr;
+}
+
+}  // namespace
 
 namespace obc_rows {
-size_t rank1_workspace_bytes(int R, int d);
-int rank1_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, int R, int d, int k_steps,
-                 int nm_n, int nm_m, const int32_t *stop_counts, const float *delta,
-                 const float *offset, int maxq, const uint8_t *live, int32_t *order, float *loss,
-                 int32_t *codes, float *W_out, float *trace, int out_ld, void *ws, size_t ws_bytes);
 
-size_t blocked_workspace_bytes(int R, int d) { return obc_align_up((size_t)R * d * d * sizeof(float), 256); }
+int blocked_max_d() { return kVariants[kNumVariants - 1].cap; }
+
+size_t blocked_workspace_bytes(int R, int d) { return carve(nullptr, nullptr, R, d); }
 
 int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, int R, int d, int k_steps,
                    int nm_n, int nm_m, const int32_t *stop_counts, const float *delta,
                    const float *offset, int maxq, const uint8_t *live, int32_t *order, float *loss,
                    int32_t *codes, float *W_out, float *trace, int out_ld, void *ws, size_t ws_bytes)
 {
-    return rank1_launch(ctx, mode, W, Hinv, R, d, k_steps, nm_n, nm_m, stop_counts, delta, offset, maxq,
-                        live, order, loss, codes, W_out, trace, out_ld, ws, ws_bytes);
+    if (d > blocked_max_d())
+        return obc_fail(ctx, OBC_ERR_BAD_SHAPE, "row solver (blocked): d = %d exceeds the supported %d", d, blocked_max_d());
+    BlockedWs bw;
+    size_t need = carve(&bw, ws, R, d);
+    if (!ws || ws_bytes < need)
+        return obc_fail(ctx, OBC_ERR_WORKSPACE, "row solver: workspace of %zu bytes needed, %zu given", need, ws_bytes);
+    hipStream_t st = ctx->stream;
+
+    InitArgs ia;
+    ia.W = W; ia.Hinv = Hinv; ia.live_in = live; ia.stop_counts = stop_counts; ia.d = d;
+    ia.k_steps = k_steps; ia.mode = mode; ia.ws = bw; ia.codes = codes; ia.W_out = W_out;
+    blocked_init_kernel<<<R, 256, 0, st>>>(ia);
+    OBC_LAUNCH_CHECK(ctx, "blocked_init_kernel");
+    if (trace && k_steps > 0) {
+        size_t n = (size_t)R * out_ld * d;
+        unsigned blocks = (unsigned)((n + 256 * 16 - 1) / (256 * 16));
+        if (blocks > 65535) blocks = 65535;
+        fill_f32_kernel<<<blocks, 256, 0, st>>>(trace, n, 0.f);
+        OBC_LAUNCH_CHECK(ctx, "fill_f32_kernel");
+    }
+
+    PanelArgs pa;
+    pa.d = d; pa.nm_n = nm_n; pa.nm_m = nm_m; pa.delta = delta; pa.offset = offset; pa.maxq = maxq;
+    pa.ws = bw; pa.order = order; pa.loss = loss; pa.codes = codes; pa.W_out = W_out; pa.trace = trace;
+    pa.out_ld = out_ld; pa.status = ctx->d_status;
+    FlushArgs fa;
+    fa.d = d; fa.R = R; fa.ws = bw;
+
+    const int host_total = (mode == MODE_QUANT) ? d : k_steps;   // upper bound over the rows
+    const size_t lds_nm = nm_m > 0 ? obc_align_up((size_t)(d / nm_m), 16) : 0;
+    int host_done = 0;
+    int cur = -1;            // -1: the shared H^-1; otherwise index into Abuf
+    int ld_cur = d;
+    while (host_done < host_total) {
+        const int m_max = d - host_done;
+        const Variant *v = pick_variant(m_max);
+        pa.A_cur = (cur < 0) ? Hinv : bw.Abuf[cur];
+        pa.a_row_stride = (cur < 0) ? 0 : (size_t)d * d;
+        pa.ld = ld_cur;
+        v->launch(mode, R, lds_nm, st, pa);
+        OBC_LAUNCH_CHECK(ctx, "panel_kernel");
+        host_done += v->B;
+        if (host_done >= host_total) break;
+        const int m_next = d - host_done;
+        const int nxt = (cur < 0) ? 0 : 1 - cur;
+        fa.A_old = pa.A_cur;
+        fa.old_row_stride = pa.a_row_stride;
+        fa.ld_old = ld_cur;
+        fa.A_new = bw.Abuf[nxt];
+        fa.new_row_stride = (size_t)d * d;
+        fa.ld_new = (m_next + 3) & ~3;
+        fa.strips = (m_next + FT - 1) / FT;
+        const int rows8 = (R + 7) / 8 * 8;
+        flush_kernel<<<dim3(fa.strips * rows8), 256, 0, st>>>(fa);
+        OBC_LAUNCH_CHECK(ctx, "flush_kernel");
+        cur = nxt;
+        ld_cur = fa.ld_new;
+    }
+    return OBC_OK;
 }
+
 }  // namespace obc_rows

@@ -31,7 +31,8 @@ __device__ inline float quant_code(float w, float delta, float offset, float max
 
 __device__ inline float dequant(float code, float delta, float offset)
 {
-    return __fadd_rn(offset, __fmul_rn(delta, code));
+    // the grid value in fp64, rounded once to fp32
+    return (float)((double)offset + (double)delta * (double)code);
 }
 
 // eq. (3) / eq. (7): (target - w)^2 / [H^-1]_pp

@@ -118,8 +118,9 @@ def check_row(orc, stats, mode, Hinv32, w32, g_order, g_loss, g_w, k_steps, nm=(
             stats.code_exempt += diff.size
         delta, offset, maxq = grid
         assert gc_l.min() >= 0 and gc_l.max() <= maxq
-        deq = np.float32(offset) + np.float32(delta) * gc_l.astype(np.float32)
-        assert np.array_equal(gw_l.astype(np.float32), deq.astype(np.float32))
+        # the stored weight is the grid value (fp64 arithmetic on the fp32 grid) rounded to fp32
+        deq = (np.float64(offset) + np.float64(delta) * gc_l.astype(np.float64)).astype(np.float32)
+        assert np.array_equal(gw_l.astype(np.float32), deq)
     if g_trace is not None and mode == "prune":
         gt = np.asarray(g_trace[:k_steps], np.float64)
         num = np.linalg.norm(gt - r.trace, axis=1)
