@@ -139,7 +139,6 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
         for (int r = 0; r < S; ++r) c = fmaf(-sh.cvec[r], st.u[r][e], c);
         st.u[S][e] = c;
         int j = tid + e * T;
-        if (j < pr.m) pr.gU[(size_t)S * pr.d + j] = c;
         if (st.alive[e]) {
             if (j == p) {
                 st.alive[e] = false;
@@ -253,6 +252,10 @@ __global__ __launch_bounds__(T) void panel_kernel(PanelArgs a)
             go[jn] = st.og[e];
             gmap[jn] = j;
             if (st.og[e] >= 0) Wo[st.og[e]] = (float)st.w[e];
+            // this block's vectors u_r, already in the new compact order, for the flush
+#pragma unroll
+            for (int r = 0; r < B; ++r)
+                if (r < nbv) pr.gU[(size_t)r * d + jn] = st.u[r][e];
         }
     }
     for (int b = tid; b < nmb; b += T) a.ws.blk[(size_t)row * d + b] = blk[b];

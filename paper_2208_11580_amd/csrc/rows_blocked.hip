@@ -129,10 +129,23 @@ struct FlushArgs {
     BlockedWs ws;
 };
 
-__global__ __launch_bounds__(256) void flush_kernel(FlushArgs a)
+// One workgroup (8 waves) per 128-row strip of one row's matrix; it walks the strip's 128-column
+// tiles.  Wave (wm, wn) owns a 64 x 32 sub-tile = two 32x32 MFMA accumulators, which are loaded
+// straight from the old matrix (one dword per lane: 32 consecutive columns of a row per half
+// wave, i.e. whole 128-byte lines) and stored straight to the new one.  Accesses to the matrices
+// are raw buffer loads / stores: a 32-bit byte offset per access instead of a 64-bit address
+// (register pressure), and the hardware range check (offset >= size reads 0 / drops the store)
+// replaces the per-element predicates.  The loads of the next tile are issued before the MFMAs
+// of the current one.
+constexpr unsigned kBufWord3 = 0x00020000u;   // raw buffer, 32-bit data format
+constexpr int kFar = 0x40000000;              // byte offset beyond any matrix: "out of range"
+
+template <int KMAX>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) void flush_kernel(FlushArgs a)
 {
-    __shared__ float Fs[BMAX][FLD];
-    __shared__ float Us[BMAX][FLD];
+    __shared__ float Fs[KMAX][FLD];
+    __shared__ float Us[KMAX][FLD];
+    __shared__ int rowoff_s[FT];
 
     // workgroups are dealt round-robin to the 8 XCDs: keep all strips of one row on one XCD so
     // that its U panel and index map stay in that XCD's L2
@@ -147,79 +160,99 @@ __global__ __launch_bounds__(256) void flush_kernel(FlushArgs a)
     if (i0 >= mn) return;
 
     const int d = a.d;
-    const float *Aold = a.A_old + (size_t)row * a.old_row_stride;
-    float *Anew = a.A_new + (size_t)row * a.new_row_stride;
     const int *map = a.ws.map + (size_t)row * d;
-    const float *U = a.ws.U + (size_t)row * BMAX * d;
+    const float *U = a.ws.U + (size_t)row * BMAX * d;      // u_k in the new compact order
     const float *invd = a.ws.invd + (size_t)row * BMAX;
     const int ldo = a.ld_old, ldn = a.ld_new;
     const int nbp = (nb + 1) & ~1;
+    __amdgpu_buffer_rsrc_t rold = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(a.A_old + (size_t)row * a.old_row_stride), 0, d * d * 4, kBufWord3);
+    __amdgpu_buffer_rsrc_t rnew = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(a.A_new + (size_t)row * a.new_row_stride), 0, mn * ldn * 4, kBufWord3);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 2, wn = wave & 3;
+    const int jl = wn * 32 + (lane & 31);
+    const int lrow = 4 * (lane >> 5);        // the lane-dependent part of the accumulator row
 
-    // F tile: F[k][i] = -u_k[i] / a_k for the strip's rows (old compact positions via the map)
-    for (int idx = tid; idx < nbp * FT; idx += 256) {
+    // F tile: F[k][i] = -u_k[i] / a_k for the strip's rows; byte offsets of the strip's old rows
+    for (int idx = tid; idx < nbp * FT; idx += 512) {
         int k = idx / FT, i = idx % FT;
         int ii = i0 + i;
         float v = 0.f;
-        if (k < nb && ii < mn) v = -__fmul_rn(U[(size_t)k * d + map[ii]], invd[k]);
+        if (k < nb && ii < mn) v = -__fmul_rn(U[(size_t)k * d + ii], invd[k]);
         Fs[k][i] = v;
     }
-    // element offsets of the 32 matrix rows this lane holds in its accumulators
-    int roff[2][16];
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            int ii = i0 + wm * 64 + mt * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-            roff[mt][v] = (ii < mn) ? map[ii] * ldo : -1;
-        }
+    if (tid < FT) rowoff_s[tid] = (i0 + tid < mn) ? map[i0 + tid] * ldo * 4 : kFar;
 
-    for (int j0 = 0; j0 < mn; j0 += FT) {
-        __syncthreads();
-        for (int idx = tid; idx < nbp * FT; idx += 256) {
-            int k = idx / FT, j = idx % FT;
-            int jj = j0 + j;
-            float v = 0.f;
-            if (k < nb && jj < mn) v = U[(size_t)k * d + map[jj]];
-            Us[k][j] = v;
-        }
-        floatx16 acc[2][2];
-        int jcol[2], jold[2];
+    // U tile staging: KMAX x 128 floats by 512 threads
+    constexpr int UPT = KMAX * FT / 512;
+    float ureg[UPT];
+    auto fetch_u = [&](int j0) {
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            jcol[nt] = j0 + wn * 64 + nt * 32 + (lane & 31);
-            jold[nt] = (jcol[nt] < mn) ? map[jcol[nt]] : -1;
+        for (int h = 0; h < UPT; ++h) {
+            int idx = tid + h * 512;
+            int k = idx / FT, j = idx % FT;
+            ureg[h] = (k < nb && j0 + j < mn) ? U[(size_t)k * d + j0 + j] : 0.f;
         }
+    };
+    auto stash_u = [&]() {
+#pragma unroll
+        for (int h = 0; h < UPT; ++h) {
+            int idx = tid + h * 512;
+            Us[idx / FT][idx % FT] = ureg[h];
+        }
+    };
+    floatx16 acc[2], nxt[2];
+    auto fetch_c = [&](floatx16(&c)[2], int joldB) {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    acc[mt][nt][v] = (roff[mt][v] >= 0 && jold[nt] >= 0) ? Aold[(size_t)roff[mt][v] + jold[nt]] : 0.f;
-        __syncthreads();
+            for (int v = 0; v < 16; ++v) {
+                int ro = rowoff_s[wm * 64 + mt * 32 + 8 * (v >> 2) + lrow + (v & 3)];
+                c[mt][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rold, ro + joldB, 0, 0));
+            }
+    };
+    auto old_col = [&](int j) { return (j < mn) ? map[j] * 4 : kFar; };
+
+    int joldB = old_col(jl);
+    int joldB_n = old_col(FT + jl);
+    fetch_u(0);
+    __syncthreads();                           // rowoff_s visible
+    fetch_c(acc, joldB);
+    stash_u();
+    for (int j0 = 0; j0 < mn; j0 += FT) {
+        __syncthreads();                       // Us (and, first time, Fs) visible
+        const bool more = j0 + FT < mn;
+        if (more) {
+            fetch_u(j0 + FT);
+            fetch_c(nxt, joldB_n);
+            joldB_n = old_col(j0 + 2 * FT + jl);
+        }
         const int kl = lane >> 5, il = lane & 31;
         for (int kk = 0; kk < nbp; kk += 2) {
             float a0 = Fs[kk + kl][wm * 64 + il];
             float a1 = Fs[kk + kl][wm * 64 + 32 + il];
-            float b0 = Us[kk + kl][wn * 64 + il];
-            float b1 = Us[kk + kl][wn * 64 + 32 + il];
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+            float b0 = Us[kk + kl][wn * 32 + il];
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1], 0, 0, 0);
         }
+        const int jcol = j0 + jl;
+        const int lanepart = (jcol < mn) ? (lrow * ldn + jcol) * 4 : kFar;
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    int ii = i0 + wm * 64 + mt * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                    if (ii < mn && jcol[nt] < mn) Anew[(size_t)ii * ldn + jcol[nt]] = acc[mt][nt][v];
-                }
+            for (int v = 0; v < 16; ++v) {
+                int rbase = (i0 + wm * 64 + mt * 32 + 8 * (v >> 2) + (v & 3)) * ldn * 4;   // uniform
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[mt][v]), rnew, rbase + lanepart, 0, 0);
+            }
+        __syncthreads();                       // everyone is done reading Us
+        if (more) {
+            stash_u();
+            acc[0] = nxt[0];
+            acc[1] = nxt[1];
+        }
     }
 }
 
@@ -311,7 +344,10 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
         fa.ld_new = (m_next + 3) & ~3;
         fa.strips = (m_next + FT - 1) / FT;
         const int rows8 = (R + 7) / 8 * 8;
-        flush_kernel<<<dim3(fa.strips * rows8), 256, 0, st>>>(fa);
+        if (v->B <= 32)
+            flush_kernel<32><<<dim3(fa.strips * rows8), 512, 0, st>>>(fa);
+        else
+            flush_kernel<64><<<dim3(fa.strips * rows8), 512, 0, st>>>(fa);
         OBC_LAUNCH_CHECK(ctx, "flush_kernel");
         cur = nxt;
         ld_cur = fa.ld_new;
