@@ -128,31 +128,44 @@ def main():
         one_step(False)
     ctx.obc_check()
     torch.cuda.synchronize()
+    ctx.obc_profile_begin()       # events around every row-solver launch, on the library's stream
     t0 = time.perf_counter()
     for _ in range(args.steps):
         result = one_step(True)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    kstats = ctx.obc_profile_end()
     ctx.obc_check()
     ms_per_step = 1e3 * wall / args.steps
     value = row_steps / (wall / args.steps)
 
-    # ---- roofline of the dominant kernel (the row solver).  Algorithmic bytes: every greedy step
-    # must read and write the live part of the row's private inverse, 8 m^2 bytes at live size m.
+    # ---- roofline of the dominant kernel of the row solver, from the events the library recorded
+    # around each of its launches during the timed steps.  Algorithmic bytes / flops per launch are
+    # those of the schedule the kernel implements (see include/obc.h, obc_profile_end).
     rows_s = 1e-3 * float(np.mean(stage_ms["rows"]))
-    m = np.arange(d, d - k_steps, -1, dtype=np.float64)
-    alg_bytes = float(R) * float(np.sum(8.0 * m * m))
-    alg_flops = float(R) * float(np.sum(2.0 * m * m))
-    info = pkg.rows_model(R, d, k_steps, strategy) if hasattr(pkg, "rows_model") else None
-    roofline = {
-        "bound": "hbm", "kernel": "rows_rank1_kernel", "achieved": alg_bytes / rows_s / 1e9,
-        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": alg_bytes / rows_s / 1e9 / HBM_PEAK_GBS,
-        "traffic": None, "model": "live-set rank-1: 8*m^2 bytes per row-step at live size m",
-        "launch_ms": 1e3 * rows_s, "row_steps_per_s_kernel": row_steps / rows_s,
-        "alg_tflops": alg_flops / rows_s / 1e12,
-    }
-    if info:
-        roofline.update(info(rows_s))
+    kern = {k: v for k, v in kstats.items() if v["launches"] > 0}
+    dom = max(kern, key=lambda k: kern[k]["ms"])
+    ds = kern[dom]
+    per_launch_ms = ds["ms"] / ds["launches"]
+    gbs = ds["bytes"] / (1e-3 * ds["ms"]) / 1e9 if ds["ms"] > 0 else 0.0
+    tfs = ds["flops"] / (1e-3 * ds["ms"]) / 1e12 if ds["ms"] > 0 else 0.0
+    names = {"flush": "flush_kernel", "panel": "panel_kernel", "rank1": "rows_rank1_kernel"}
+    if dom == "rank1" and ds["bytes"] == 0:      # LDS-resident: bounded by the fp32 vector units
+        roofline = {"bound": "alu", "kernel": names[dom], "achieved": tfs, "peak": 78.6, "unit": "TFLOP/s",
+                    "frac": tfs / 78.6, "traffic": None}
+    else:
+        roofline = {"bound": "hbm", "kernel": names[dom], "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": gbs / HBM_PEAK_GBS, "traffic": None}
+    roofline.update({
+        "launches_per_step": ds["launches"] / args.steps, "avg_launch_ms": per_launch_ms,
+        "alg_bytes_per_launch": ds["bytes"] / ds["launches"], "mfma_tflops": tfs,
+        "mfma_frac": tfs / MFMA_F32_PEAK_TFLOPS,
+        "share_of_rows_time": ds["ms"] / args.steps / (1e3 * rows_s),
+        "row_steps_per_s_rows_call": row_steps / rows_s,
+        "kernels": {names[k]: {"launches_per_step": v["launches"] / args.steps, "ms_per_step": v["ms"] / args.steps,
+                               "GB/s": v["bytes"] / (1e-3 * v["ms"]) / 1e9, "TFLOP/s": v["flops"] / (1e-3 * v["ms"]) / 1e12}
+                    for k, v in kern.items()},
+    })
 
     line = {
         "metric": "ExactOBS row-steps/sec per layer + % fp32 VALU/HBM roofline, 1 MI355X",

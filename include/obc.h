@@ -61,6 +61,27 @@ const char *obc_version(void);
  * obc_check (OBC_ERR_NUMERIC, OBC_ERR_NOT_SPD) or OBC_OK; clears the latch. */
 int obc_check(obc_ctx *ctx);
 
+/* ---- Measurement support (not part of the method) ---------------------------------------
+ * Between obc_profile_begin and obc_profile_end every launch of the row solvers' kernels is
+ * bracketed by HIP events on the context's stream.  obc_profile_end waits for the stream and
+ * fills one obc_kernel_stat per kernel class: launches, summed duration, and the algorithmic
+ * bytes / flops of those launches (what the method needs moved / computed under the schedule
+ * the kernel implements: the flush reads and writes the surviving m x m part of each row's
+ * inverse once per block, 8 m^2 bytes and 2 B m^2 flops per row; a panel reads one matrix row
+ * per step; the rank-1 kernel moves 8 m^2 bytes per step). */
+#define OBC_KERNEL_PANEL 0
+#define OBC_KERNEL_FLUSH 1
+#define OBC_KERNEL_RANK1 2
+#define OBC_KERNEL_CLASSES 3
+typedef struct obc_kernel_stat {
+    int launches;
+    double ms;
+    double bytes;
+    double flops;
+} obc_kernel_stat;
+int obc_profile_begin(obc_ctx *ctx);
+int obc_profile_end(obc_ctx *ctx, obc_kernel_stat stats[OBC_KERNEL_CLASSES]);
+
 /* ---- Sec. 4: H = 2 X X^T, "Implementation Details": dampening -------------------------
  * X: d x N fp32 with leading dimension ldx >= N (element (j, n) at X[j*ldx + n]).
  * H: d x d fp32.  accumulate == 0: H = 2 X X^T;  accumulate != 0: H += 2 X X^T (calibration

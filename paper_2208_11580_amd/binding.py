@@ -23,11 +23,20 @@ STRATEGY_AUTO, STRATEGY_RANK1, STRATEGY_BLOCKED = 0, 1, 2
 
 EXPORTS = [
     "obc_create", "obc_destroy", "obc_last_error", "obc_version", "obc_check",
+    "obc_profile_begin", "obc_profile_end",
     "obc_hessian_workspace_bytes", "obc_hessian",
     "obc_invert_workspace_bytes", "obc_invert",
     "obc_rows_workspace_bytes", "obc_prune_rows", "obc_quant_rows", "obc_minmax_grid",
     "obc_global_select_workspace_bytes", "obc_global_select", "obc_gather_trace",
 ]
+
+
+KERNEL_CLASSES = ("panel", "flush", "rank1")
+
+
+class KernelStat(ctypes.Structure):
+    _fields_ = [("launches", c_int), ("ms", ctypes.c_double), ("bytes", ctypes.c_double),
+                ("flops", ctypes.c_double)]
 
 
 class ObcError(RuntimeError):
@@ -57,6 +66,8 @@ def load_library():
     lib.obc_version.argtypes = []
     lib.obc_version.restype = c_char_p
     lib.obc_check.argtypes = [vp]
+    lib.obc_profile_begin.argtypes = [vp]
+    lib.obc_profile_end.argtypes = [vp, POINTER(KernelStat)]
     lib.obc_hessian_workspace_bytes.argtypes = [c_int, c_int64, sp]
     lib.obc_hessian.argtypes = [vp, vp, c_int, c_int64, c_int64, c_float, c_int, vp, vp, c_size_t]
     lib.obc_invert_workspace_bytes.argtypes = [c_int, sp]
@@ -132,6 +143,15 @@ class Context:
     # ------------------------------------------------------------------ entry points
     def obc_check(self):
         self._ck(self.lib.obc_check(self.h))
+
+    def obc_profile_begin(self):
+        self._ck(self.lib.obc_profile_begin(self.h))
+
+    def obc_profile_end(self):
+        arr = (KernelStat * len(KERNEL_CLASSES))()
+        self._ck(self.lib.obc_profile_end(self.h, arr))
+        return {name: dict(launches=arr[i].launches, ms=arr[i].ms, bytes=arr[i].bytes, flops=arr[i].flops)
+                for i, name in enumerate(KERNEL_CLASSES)}
 
     def obc_hessian(self, X, damp_rel=0.01, H=None, accumulate=False):
         d, N = X.shape

@@ -8,14 +8,53 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "../../include/obc.h"
+
+// One timed kernel launch (only while profiling is on): events on the context's stream.
+struct obc_timed {
+    hipEvent_t start, stop;
+    int kind;           // OBC_KERNEL_*
+    double bytes, flops;   // algorithmic work of the launch
+};
 
 struct obc_ctx {
     hipStream_t stream;
     int device;
     int *d_status;      // device error latch: 0, or the first OBC_ERR_* a kernel saw
     char err[512];
+    bool profiling;
+    std::vector<obc_timed> timed;
+    std::vector<hipEvent_t> event_pool;
+};
+
+// Bracket a launch with events when profiling is on.
+struct obc_scope {
+    obc_ctx *ctx;
+    obc_timed t;
+    bool on;
+    obc_scope(obc_ctx *c, int kind, double bytes, double flops) : ctx(c), on(c->profiling)
+    {
+        if (!on) return;
+        t.kind = kind; t.bytes = bytes; t.flops = flops;
+        auto get = [&]() {
+            hipEvent_t e;
+            if (!ctx->event_pool.empty()) { e = ctx->event_pool.back(); ctx->event_pool.pop_back(); return e; }
+            if (hipEventCreate(&e) != hipSuccess) e = nullptr;
+            return e;
+        };
+        t.start = get();
+        t.stop = get();
+        if (!t.start || !t.stop) { on = false; return; }
+        (void)hipEventRecord(t.start, ctx->stream);
+    }
+    ~obc_scope()
+    {
+        if (!on) return;
+        (void)hipEventRecord(t.stop, ctx->stream);
+        ctx->timed.push_back(t);
+    }
 };
 
 static inline int obc_fail(obc_ctx *ctx, int code, const char *fmt, ...)

@@ -330,7 +330,13 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
         pa.A_cur = (cur < 0) ? Hinv : bw.Abuf[cur];
         pa.a_row_stride = (cur < 0) ? 0 : (size_t)d * d;
         pa.ld = ld_cur;
-        v->launch(mode, R, lds_nm, st, pa);
+        {
+            // a panel reads one (corrected) matrix row per step: 4 m bytes, and does ~B m flops on it
+            const int steps = (host_total - host_done < v->B) ? host_total - host_done : v->B;
+            obc_scope sc(ctx, OBC_KERNEL_PANEL, (double)R * steps * 4.0 * m_max,
+                         (double)R * steps * (double)steps * m_max);
+            v->launch(mode, R, lds_nm, st, pa);
+        }
         OBC_LAUNCH_CHECK(ctx, "panel_kernel");
         host_done += v->B;
         if (host_done >= host_total) break;
@@ -344,10 +350,15 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
         fa.ld_new = (m_next + 3) & ~3;
         fa.strips = (m_next + FT - 1) / FT;
         const int rows8 = (R + 7) / 8 * 8;
-        if (v->B <= 32)
-            flush_kernel<32><<<dim3(fa.strips * rows8), 512, 0, st>>>(fa);
-        else
-            flush_kernel<64><<<dim3(fa.strips * rows8), 512, 0, st>>>(fa);
+        {
+            // the surviving m_next x m_next part of every row's inverse is read and written once
+            obc_scope sc(ctx, OBC_KERNEL_FLUSH, (double)R * 8.0 * m_next * m_next,
+                         (double)R * 2.0 * v->B * (double)m_next * m_next);
+            if (v->B <= 32)
+                flush_kernel<32><<<dim3(fa.strips * rows8), 512, 0, st>>>(fa);
+            else
+                flush_kernel<64><<<dim3(fa.strips * rows8), 512, 0, st>>>(fa);
+        }
         OBC_LAUNCH_CHECK(ctx, "flush_kernel");
         cur = nxt;
         ld_cur = fa.ld_new;

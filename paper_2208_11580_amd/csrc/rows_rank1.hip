@@ -261,6 +261,10 @@ int rank1_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, int 
         return obc_fail(ctx, OBC_ERR_BAD_SHAPE, "row solver (rank-1): d = %d needs %zu bytes of LDS", d, lds);
     const int threads = d <= 64 ? 256 : (d <= 192 ? 512 : 1024);
     if (R == 0) return OBC_OK;
+    // live-set model of Algorithm 1: step t reads and writes the (d - t)^2 live entries
+    double mm = 0.0;
+    for (int t = 0; t < k_steps; ++t) mm += (double)(d - t) * (double)(d - t);
+    obc_scope sc(ctx, OBC_KERNEL_RANK1, resident ? 0.0 : (double)R * 8.0 * mm, (double)R * 2.0 * mm);
     if (mode == MODE_PRUNE) {
         OBC_HIP(ctx, hipFuncSetAttribute((const void *)rows_rank1_kernel<MODE_PRUNE>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
