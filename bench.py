@@ -47,6 +47,9 @@ def main():
     ap.add_argument("--strategy", default="auto", choices=["auto", "rank1", "blocked"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows in the oracle sample (0 = one per host thread)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="after the timed region run one plain 1 GiB device copy (calibrates rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters against a kernel of known traffic)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the row solver shards trivially over rows, "
@@ -138,6 +141,12 @@ def main():
     ctx.obc_check()
     ms_per_step = 1e3 * wall / args.steps
     value = row_steps / (wall / args.steps)
+    if args.calib_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB read, 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- roofline of the dominant kernel of the row solver, from the events the library recorded
     # around each of its launches during the timed steps.  Algorithmic bytes / flops per launch are

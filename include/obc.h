@@ -66,9 +66,9 @@ int obc_check(obc_ctx *ctx);
  * bracketed by HIP events on the context's stream.  obc_profile_end waits for the stream and
  * fills one obc_kernel_stat per kernel class: launches, summed duration, and the algorithmic
  * bytes / flops of those launches (what the method needs moved / computed under the schedule
- * the kernel implements: the flush reads and writes the surviving m x m part of each row's
- * inverse once per block, 8 m^2 bytes and 2 B m^2 flops per row; a panel reads one matrix row
- * per step; the rank-1 kernel moves 8 m^2 bytes per step). */
+ * the kernel implements: the flush reads and writes one triangle of the surviving m x m part of
+ * each row's (symmetric) inverse once per block of B steps, 8 m(m+1)/2 bytes and B m(m+1) flops
+ * per row; a panel reads one matrix row per step; the rank-1 kernel moves 8 m^2 bytes per step). */
 #define OBC_KERNEL_PANEL 0
 #define OBC_KERNEL_FLUSH 1
 #define OBC_KERNEL_RANK1 2

@@ -6,92 +6,167 @@
 
 namespace obc_blocked {
 
+// Phase timing of the panel kernel for kernel development: compiled in only with
+// -DOBC_PANEL_TIMING; thread 0 of workgroup 0 accumulates shader-clock deltas per phase.
+#ifdef OBC_PANEL_TIMING
+extern __device__ unsigned long long obc_panel_timing[8];
+#define OBC_TICK(slot)                                                        \
+    do {                                                                      \
+        if (blockIdx.x == 0 && threadIdx.x == 0) {                            \
+            unsigned long long now__ = __builtin_readcyclecounter();          \
+            atomicAdd(&obc_panel_timing[slot], now__ - pr.tick);              \
+            const_cast<PanelRow &>(pr).tick = now__;                          \
+        }                                                                     \
+    } while (0)
+#else
+#define OBC_TICK(slot) do { } while (0)
+#endif
+
 // Per-thread state of the panel: everything indexed by the owned element e (compact index
 // tid + e*T) or by the step r inside the block.  All indices are compile-time constants once the
 // step loop is unrolled (panel_steps below), so the arrays live in registers.
-template <int EPT, int B>
+template <int EPT, int BR>
 struct PanelRegs {
     double w[EPT], dg[EPT];
     int og[EPT];
     bool alive[EPT];
-    float u[B][EPT];
+    float u[BR][EPT];   // u_r for the first BR steps of the block; later ones live in LDS
 };
 
 struct PanelShared {
-    double red_s[2][16];
-    int red_j[2][16];
-    float cvec[BMAX];
+    unsigned long long red_k[2][16];
+    __attribute__((aligned(16))) float cvec[BMAX];
     float invd_s[BMAX];
     int pivs[BMAX];
-    double bc_wp, bc_app;
-    int bc_o;
+    double bc_g, bc_invapp;
+    int bc_o, bc_ok;
 };
+
+// order-preserving map of a float onto unsigned integers
+__device__ __forceinline__ unsigned score_bits(float f)
+{
+    unsigned u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// one DPP stage of a 64-bit unsigned minimum: combine with the lane `row_shr` positions down the
+// 16-lane row (lanes shifted in from outside the row contribute the identity)
+template <int CTRL>
+__device__ __forceinline__ unsigned long long dpp_min_stage(unsigned long long k)
+{
+    unsigned lo = (unsigned)k, hi = (unsigned)(k >> 32);
+    unsigned olo = (unsigned)__builtin_amdgcn_update_dpp(-1, (int)lo, CTRL, 0xf, 0xf, false);
+    unsigned ohi = (unsigned)__builtin_amdgcn_update_dpp(-1, (int)hi, CTRL, 0xf, 0xf, false);
+    unsigned long long o = ((unsigned long long)ohi << 32) | olo;
+    return o < k ? o : k;
+}
+
+// minimum over each 16-lane row, returned from the row's last lane of the caller's choice
+__device__ __forceinline__ unsigned long long row16_reduce(unsigned long long k)
+{
+    k = dpp_min_stage<0x111>(k);   // row_shr:1
+    k = dpp_min_stage<0x112>(k);   // row_shr:2
+    k = dpp_min_stage<0x114>(k);   // row_shr:4
+    k = dpp_min_stage<0x118>(k);   // row_shr:8
+    return k;                      // lane 15 of every row holds the row's minimum
+}
+
+__device__ __forceinline__ unsigned long long read_lane_key(unsigned long long k, int l)
+{
+    unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)k, l);
+    unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(k >> 32), l);
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+// minimum over the wavefront (uniform result)
+__device__ __forceinline__ unsigned long long wave_min_key(unsigned long long k)
+{
+    k = row16_reduce(k);
+    unsigned long long a0 = read_lane_key(k, 15), a1 = read_lane_key(k, 31);
+    unsigned long long a2 = read_lane_key(k, 47), a3 = read_lane_key(k, 63);
+    a0 = a1 < a0 ? a1 : a0;
+    a2 = a3 < a2 ? a3 : a2;
+    return a2 < a0 ? a2 : a0;
+}
+
+// minimum over the first 16 lanes' values (every row holds the same 16 values; uniform result)
+__device__ __forceinline__ unsigned long long row16_min_key(unsigned long long k)
+{
+    k = row16_reduce(k);
+    return read_lane_key(k, 15);
+}
 
 struct PanelRow {
     const float *Acur;
     float *gU;
     int ld, d, m, done, total, ndead, row;
-    double qd, qo, qmax;
+    double qd, qo, qmax, iqd;
+    unsigned long long tick;
 };
 
 // One greedy step, S-th of the block.  Returns 0 to continue, 1 when the row has no step left,
 // 2 on a numeric failure.  Every thread of the workgroup returns the same value.
-template <int MODE, int T, int EPT, int B, int S>
-__device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr, PanelRegs<EPT, B> &st,
-                                          PanelShared &sh, uint8_t *blk)
+template <int MODE, int T, int EPT, int BR, int BL, int S>
+__device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr, PanelRegs<EPT, BR> &st,
+                                          PanelShared &sh, uint8_t *blk, float *ul)
 {
+    // u_r[j] for r >= BR is kept at ul[(r - BR) * (T * EPT) + j]; only the owner of j touches it
+    constexpr int CAP = T * EPT;
     constexpr int NW = T / 64;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (pr.done + S >= pr.total) return 1;
+    OBC_TICK(0);   // since the end of the previous step
 
-    // ---- (1) selection: fp64 score of every owned live index, workgroup argmin
-    double bs = __builtin_inf();
-    int bj = 0x7fffffff;
+    // ---- (1) selection.  The error (target - w) is formed in fp64 (for OBQ it is a difference of
+    // nearby numbers); the score itself, error^2 / a_jj, is only compared, so it is taken in fp32
+    // with the hardware reciprocal (2 ulp): candidates closer than that count as tied.
+    // A candidate is the 64-bit key (order-preserving bits of the score, index): the unsigned
+    // minimum of the keys is the argmin with ties to the lowest index.
+    unsigned long long key = ~0ull;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
         if (!st.alive[e]) continue;
-        double sc;
+        float sc;
         if (st.og[e] < 0) {
-            sc = -1.0;
+            sc = -1.f;
         } else {
             if (a.nm_m > 0 && blk[st.og[e] / a.nm_m] >= a.nm_m - a.nm_n) continue;
             double tq = 0.0;
             if (MODE == MODE_QUANT) {
-                double c = rint((st.w[e] - pr.qo) / pr.qd);
+                double c = rint((st.w[e] - pr.qo) * pr.iqd);
                 c = fmin(fmax(c, 0.0), pr.qmax);
                 tq = pr.qo + pr.qd * c;
             }
             double er = tq - st.w[e];
-            sc = er * er / st.dg[e];
+            sc = (float)(er * er) * __builtin_amdgcn_rcpf((float)st.dg[e]);
         }
-        if (sc < bs) { bs = sc; bj = tid + e * T; }   // own indices ascend: strict '<' keeps the lowest
+        if (sc == sc) {   // a NaN score is no candidate
+            unsigned long long k = ((unsigned long long)score_bits(sc) << 32) | (unsigned)(tid + e * T);
+            key = k < key ? k : key;
+        }
     }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        double os = __shfl_xor(bs, off, 64);
-        int oj = __shfl_xor(bj, off, 64);
-        if (os < bs || (os == bs && oj < bj)) { bs = os; bj = oj; }
-    }
-    if (lane == 0) { sh.red_s[S & 1][wave] = bs; sh.red_j[S & 1][wave] = bj; }
+    key = wave_min_key(key);
+    if (lane == 0) sh.red_k[S & 1][wave] = key;
+    OBC_TICK(1);   // selection + wave reduction
     __syncthreads();
-    bs = sh.red_s[S & 1][0];
-    bj = sh.red_j[S & 1][0];
-#pragma unroll
-    for (int wv = 1; wv < NW; ++wv) {
-        double os = sh.red_s[S & 1][wv];
-        int oj = sh.red_j[S & 1][wv];
-        if (os < bs || (os == bs && oj < bj)) { bs = os; bj = oj; }
-    }
-    const int p = bj;
-    if (p == 0x7fffffff) return 2;
+    OBC_TICK(2);   // barrier 1
+    key = row16_min_key((lane & 15) < NW ? sh.red_k[S & 1][lane & 15] : ~0ull);
+    if (key == ~0ull) return 2;
+    const int p = (int)(unsigned)key;
 
-    // ---- (2) fetch the owned part of A0[p,:]; the owner of p publishes what everyone needs
+    // ---- (2) fetch the owned part of row p of A0.  Only the tiles on and below the block
+    // diagonal of A0 are kept up to date (the matrix is symmetric): up to the end of p's
+    // 128-wide tile the row itself is read, beyond it column p.
     float col[EPT];
+    const int pend = p | (FT - 1);
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
         int j = tid + e * T;
-        col[e] = (j < pr.m) ? pr.Acur[(size_t)p * pr.ld + j] : 0.f;
+        size_t off = (j <= pend) ? (size_t)p * pr.ld + j : (size_t)j * pr.ld + p;
+        col[e] = (j < pr.m) ? pr.Acur[off] : 0.f;
     }
+    // the owner of p publishes the pivot's data, the step's scalars and the coefficients
+    // u_r[p] / a_r of the earlier steps of this block
     const bool owner = (tid == p % T);
     if (owner) {
         const int ep = p / T;
@@ -100,45 +175,72 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
 #pragma unroll
         for (int e = 0; e < EPT; ++e)
             if (e == ep) { wp = st.w[e]; ap = st.dg[e]; op = st.og[e]; }
-        sh.bc_wp = wp;
-        sh.bc_app = ap;
+        double target = 0.0, code = 0.0;
+        if (op < 0) target = wp;
+        else if (MODE == MODE_QUANT) {
+            code = rint((wp - pr.qo) / pr.qd);
+            code = fmin(fmax(code, 0.0), pr.qmax);
+            target = pr.qo + pr.qd * code;
+        }
+        const bool ok = (ap > 0.0) && (ap < __builtin_inf());
+        const double invapp = 1.0 / ap;
+        sh.bc_g = (wp - target) / ap;
+        sh.bc_invapp = invapp;
         sh.bc_o = op;
+        sh.bc_ok = ok ? 1 : 0;
         sh.pivs[S] = p;
+        sh.invd_s[S] = (float)invapp;
 #pragma unroll
         for (int r = 0; r < S; ++r) {
             float ur = 0.f;
+            if (r < BR) {
 #pragma unroll
-            for (int e = 0; e < EPT; ++e)
-                if (e == ep) ur = st.u[r][e];
+                for (int e = 0; e < EPT; ++e)
+                    if (e == ep) ur = st.u[r < BR ? r : 0][e];
+            } else {
+                ur = ul[(r - BR) * CAP + p];
+            }
             sh.cvec[r] = __fmul_rn(ur, sh.invd_s[r]);
         }
         if (a.nm_m > 0 && op >= 0) blk[op / a.nm_m] += 1;
+        if (ok && op >= 0) {
+            const int t = pr.done + S - pr.ndead;
+            const double er = target - wp;
+            a.order[(size_t)pr.row * a.out_ld + t] = op;
+            a.loss[(size_t)pr.row * a.out_ld + t] = (float)(er * er / (2.0 * ap));
+            a.W_out[(size_t)pr.row * pr.d + op] = (float)target;
+            if (MODE == MODE_QUANT) a.codes[(size_t)pr.row * pr.d + op] = (int)code;
+        }
     }
+    OBC_TICK(3);   // cross-wave reduction, load issue, owner's publication
     __syncthreads();
-    const double app = sh.bc_app, wp = sh.bc_wp;
-    const int op = sh.bc_o;
-    if (!(app > 0.0) || !(app < __builtin_inf())) return 2;
-
-    // ---- (3) target, compensation factor
-    const bool isdead = op < 0;
-    double target = 0.0, code = 0.0;
-    if (isdead) target = wp;
-    else if (MODE == MODE_QUANT) {
-        code = rint((wp - pr.qo) / pr.qd);
-        code = fmin(fmax(code, 0.0), pr.qmax);
-        target = pr.qo + pr.qd * code;
+    OBC_TICK(4);   // barrier 2
+    if (!sh.bc_ok) return 2;
+    const double g = sh.bc_g, invapp = sh.bc_invapp;
+    const bool isdead = sh.bc_o < 0;
+    // coefficients of this step, once, into registers
+    float cv[S > 0 ? S : 1];
+#pragma unroll
+    for (int r4 = 0; r4 < S; r4 += 4) {
+        float4 c4 = *reinterpret_cast<const float4 *>(&sh.cvec[r4]);
+        cv[r4] = c4.x;
+        if (r4 + 1 < S) cv[r4 + 1] = c4.y;
+        if (r4 + 2 < S) cv[r4 + 2] = c4.z;
+        if (r4 + 3 < S) cv[r4 + 3] = c4.w;
     }
-    const double g = (wp - target) / app;
-    const double invapp = 1.0 / app;
 
-    // ---- (4) bring the fetched row up to date, keep it, update w and the diagonal
+    // ---- (3) bring the fetched row up to date, keep it, update w and the diagonal
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
         float c = col[e];
-#pragma unroll
-        for (int r = 0; r < S; ++r) c = fmaf(-sh.cvec[r], st.u[r][e], c);
-        st.u[S][e] = c;
         int j = tid + e * T;
+#pragma unroll
+        for (int r = 0; r < S; ++r) {
+            float ur = (r < BR) ? st.u[r < BR ? r : 0][e] : ul[(r - BR) * CAP + j];
+            c = fmaf(-cv[r], ur, c);
+        }
+        if constexpr (S < BR) st.u[S < BR ? S : 0][e] = c;
+        else ul[(S - BR) * CAP + j] = c;
         if (st.alive[e]) {
             if (j == p) {
                 st.alive[e] = false;
@@ -149,48 +251,43 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
             }
         }
     }
-    if (owner) {
-        sh.invd_s[S] = (float)invapp;
-        if (!isdead) {
-            const int t = pr.done + S - pr.ndead;
-            const double er = target - wp;
-            a.order[(size_t)pr.row * a.out_ld + t] = op;
-            a.loss[(size_t)pr.row * a.out_ld + t] = (float)(er * er / (2.0 * app));
-            a.W_out[(size_t)pr.row * pr.d + op] = (float)target;
-            if (MODE == MODE_QUANT) a.codes[(size_t)pr.row * pr.d + op] = (int)code;
-        }
-    }
+    OBC_TICK(5);   // wait for the row, correction, w / diag update
     if (MODE == MODE_PRUNE && a.trace && !isdead) {
         float *tr = a.trace + ((size_t)pr.row * a.out_ld + (pr.done + S - pr.ndead)) * pr.d;
 #pragma unroll
         for (int e = 0; e < EPT; ++e)
             if (st.alive[e] && st.og[e] >= 0) tr[st.og[e]] = (float)st.w[e];
     }
+    OBC_TICK(6);   // records, trace
     return 0;
 }
 
 // Compile-time unrolled step loop; returns the number of steps done and sets *failed.
-template <int MODE, int T, int EPT, int B, int S>
-__device__ __forceinline__ int panel_steps(const PanelArgs &a, const PanelRow &pr, PanelRegs<EPT, B> &st,
-                                           PanelShared &sh, uint8_t *blk, bool *failed)
+template <int MODE, int T, int EPT, int BR, int BL, int S>
+__device__ __forceinline__ int panel_steps(const PanelArgs &a, const PanelRow &pr, PanelRegs<EPT, BR> &st,
+                                           PanelShared &sh, uint8_t *blk, float *ul, bool *failed)
 {
-    if constexpr (S < B) {
-        int rc = panel_step<MODE, T, EPT, B, S>(a, pr, st, sh, blk);
+    if constexpr (S < BR + BL) {
+        int rc = panel_step<MODE, T, EPT, BR, BL, S>(a, pr, st, sh, blk, ul);
         if (rc != 0) {
             *failed = (rc == 2);
             return S;
         }
-        return panel_steps<MODE, T, EPT, B, S + 1>(a, pr, st, sh, blk, failed);
+        return panel_steps<MODE, T, EPT, BR, BL, S + 1>(a, pr, st, sh, blk, ul, failed);
     } else {
-        return B;
+        return BR + BL;
     }
 }
 
-template <int MODE, int T, int EPT, int B>
+template <int MODE, int T, int EPT, int BR, int BL>
 __global__ __launch_bounds__(T) void panel_kernel(PanelArgs a)
 {
+    constexpr int B = BR + BL;
     __shared__ PanelShared sh;
-    extern __shared__ uint8_t blk[];   // N:M counters (d / M bytes), only when nm_m > 0
+    // dynamic LDS: BL vectors of T * EPT floats, then the N:M counters (d / M bytes) when nm_m > 0
+    extern __shared__ __align__(16) uint8_t dyn_lds[];
+    float *ul = reinterpret_cast<float *>(dyn_lds);
+    uint8_t *blk = dyn_lds + (size_t)BL * T * EPT * sizeof(float);
 
     const int row = blockIdx.x, tid = threadIdx.x;
     PanelRow pr;
@@ -212,7 +309,7 @@ __global__ __launch_bounds__(T) void panel_kernel(PanelArgs a)
     double *gd = a.ws.diag + (size_t)row * d;
     int *go = a.ws.orig + (size_t)row * d;
 
-    PanelRegs<EPT, B> st;
+    PanelRegs<EPT, BR> st;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
         int j = tid + e * T;
@@ -227,10 +324,12 @@ __global__ __launch_bounds__(T) void panel_kernel(PanelArgs a)
     pr.qo = 0.0;
     pr.qmax = (double)a.maxq;
     if (MODE == MODE_QUANT) { pr.qd = (double)a.delta[row]; pr.qo = (double)a.offset[row]; }
+    pr.iqd = 1.0 / pr.qd;
+    pr.tick = __builtin_readcyclecounter();
     __syncthreads();
 
     bool failed = false;
-    const int nbv = panel_steps<MODE, T, EPT, B, 0>(a, pr, st, sh, blk, &failed);
+    const int nbv = panel_steps<MODE, T, EPT, BR, BL, 0>(a, pr, st, sh, blk, ul, &failed);
     __syncthreads();
 
     // ---- block epilogue: drop this block's pivots from the compact index space
@@ -255,7 +354,8 @@ __global__ __launch_bounds__(T) void panel_kernel(PanelArgs a)
             // this block's vectors u_r, already in the new compact order, for the flush
 #pragma unroll
             for (int r = 0; r < B; ++r)
-                if (r < nbv) pr.gU[(size_t)r * d + jn] = st.u[r][e];
+                if (r < nbv)
+                    pr.gU[(size_t)r * d + jn] = (r < BR) ? st.u[r < BR ? r : 0][e] : ul[(r - BR) * (T * EPT) + j];
         }
     }
     for (int b = tid; b < nmb; b += T) a.ws.blk[(size_t)row * d + b] = blk[b];
@@ -271,14 +371,24 @@ __global__ __launch_bounds__(T) void panel_kernel(PanelArgs a)
 }
 
 
-#define OBC_DEFINE_PANEL(T, EPT, B)                                                                 \
-    void launch_panel_##T##_##EPT##_##B(int mode, int R, size_t lds, hipStream_t st,                \
-                                        const PanelArgs &a)                                         \
+#define OBC_DEFINE_PANEL(T, EPT, BR, BL)                                                            \
+    int launch_panel_##T##_##EPT##_##BR##_##BL(int mode, int R, size_t lds_nm, hipStream_t st,      \
+                                               const PanelArgs &a)                                  \
     {                                                                                               \
-        if (mode == MODE_PRUNE)                                                                     \
-            hipLaunchKernelGGL((panel_kernel<MODE_PRUNE, T, EPT, B>), dim3(R), dim3(T), lds, st, a); \
-        else                                                                                        \
-            hipLaunchKernelGGL((panel_kernel<MODE_QUANT, T, EPT, B>), dim3(R), dim3(T), lds, st, a); \
+        const size_t lds = (size_t)(BL) * (T) * (EPT) * sizeof(float) + lds_nm;                     \
+        auto kp = panel_kernel<MODE_PRUNE, T, EPT, BR, BL>;                                         \
+        auto kq = panel_kernel<MODE_QUANT, T, EPT, BR, BL>;                                         \
+        static bool attr_set = false;                                                               \
+        if (!attr_set && lds > 48 * 1024) {                                                         \
+            if (hipFuncSetAttribute((const void *)kp, hipFuncAttributeMaxDynamicSharedMemorySize,   \
+                                    (int)(160 * 1024 - 2048)) != hipSuccess) return -1;             \
+            if (hipFuncSetAttribute((const void *)kq, hipFuncAttributeMaxDynamicSharedMemorySize,   \
+                                    (int)(160 * 1024 - 2048)) != hipSuccess) return -1;             \
+            attr_set = true;                                                                        \
+        }                                                                                           \
+        if (mode == MODE_PRUNE) hipLaunchKernelGGL(kp, dim3(R), dim3(T), lds, st, a);               \
+        else hipLaunchKernelGGL(kq, dim3(R), dim3(T), lds, st, a);                                  \
+        return 0;                                                                                   \
     }
 
 }  // namespace obc_blocked

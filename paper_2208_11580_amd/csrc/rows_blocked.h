@@ -51,14 +51,15 @@ struct PanelArgs {
     int *status;
 };
 
-// launchers defined in panel_<T>x<EPT>x<B>.hip
-#define OBC_DECLARE_PANEL(T, EPT, B) \
-    void launch_panel_##T##_##EPT##_##B(int mode, int R, size_t lds, hipStream_t st, const PanelArgs &a)
-OBC_DECLARE_PANEL(256, 1, 64);
-OBC_DECLARE_PANEL(1024, 1, 64);
-OBC_DECLARE_PANEL(1024, 2, 32);
-OBC_DECLARE_PANEL(768, 3, 32);
-OBC_DECLARE_PANEL(768, 4, 24);
-OBC_DECLARE_PANEL(768, 6, 16);
+// launchers defined in panel_<T>x<EPT>x<BR>x<BL>.hip: T threads, EPT owned indices per thread,
+// blocks of BR + BL steps (BR vectors in registers, BL in LDS).  Return 0 or -1 (HIP error).
+#define OBC_DECLARE_PANEL(T, EPT, BR, BL) \
+    int launch_panel_##T##_##EPT##_##BR##_##BL(int mode, int R, size_t lds_nm, hipStream_t st, const PanelArgs &a)
+OBC_DECLARE_PANEL(256, 1, 64, 0);
+OBC_DECLARE_PANEL(1024, 1, 64, 0);
+OBC_DECLARE_PANEL(1024, 2, 32, 16);
+OBC_DECLARE_PANEL(768, 3, 32, 16);
+OBC_DECLARE_PANEL(768, 4, 24, 12);
+OBC_DECLARE_PANEL(768, 6, 16, 8);
 
 }  // namespace obc_blocked

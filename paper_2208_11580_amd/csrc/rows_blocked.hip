@@ -130,7 +130,9 @@ struct FlushArgs {
 };
 
 // One workgroup (8 waves) per 128-row strip of one row's matrix; it walks the strip's 128-column
-// tiles.  Wave (wm, wn) owns a 64 x 32 sub-tile = two 32x32 MFMA accumulators, which are loaded
+// tiles up to and including the diagonal one: the matrix is symmetric, so only the tiles on and
+// below the block diagonal are kept (the panel reads row p as "row part + column part").  A
+// diagonal tile is written in full; its upper-triangle entries are read from their mirror images.  Wave (wm, wn) owns a 64 x 32 sub-tile = two 32x32 MFMA accumulators, which are loaded
 // straight from the old matrix (one dword per lane: 32 consecutive columns of a row per half
 // wave, i.e. whole 128-byte lines) and stored straight to the new one.  Accesses to the matrices
 // are raw buffer loads / stores: a 32-bit byte offset per access instead of a 64-bit address
@@ -140,21 +142,24 @@ struct FlushArgs {
 constexpr unsigned kBufWord3 = 0x00020000u;   // raw buffer, 32-bit data format
 constexpr int kFar = 0x40000000;              // byte offset beyond any matrix: "out of range"
 
+// K is the block size: every row that still has steps to do has exactly K deferred eliminations
+// (a row with fewer has finished and is skipped).
 template <int KMAX>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) void flush_kernel(FlushArgs a)
 {
     __shared__ float Fs[KMAX][FLD];
     __shared__ float Us[KMAX][FLD];
-    __shared__ int rowoff_s[FT];
+    __shared__ int rowoff_s[FT];   // byte offset of each strip row in the old matrix
+    __shared__ int rowold_s[FT];   // its old compact index
 
     // workgroups are dealt round-robin to the 8 XCDs: keep all strips of one row on one XCD so
     // that its U panel and index map stay in that XCD's L2
     const int L = blockIdx.x;
     const int row = (L / (8 * a.strips)) * 8 + (L % 8);
-    const int strip = (L / 8) % a.strips;
+    const int strip = a.strips - 1 - (L / 8) % a.strips;   // longest strips first
     if (row >= a.R) return;
-    const int nb = a.ws.nb[row];
-    if (nb == 0 || a.ws.done[row] >= a.ws.total[row]) return;
+    if (a.ws.nb[row] != KMAX || a.ws.done[row] >= a.ws.total[row]) return;
+    constexpr int nb = KMAX;
     const int mn = a.ws.m[row];             // live size after the block (new compact space)
     const int i0 = strip * FT;
     if (i0 >= mn) return;
@@ -164,7 +169,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     const float *U = a.ws.U + (size_t)row * BMAX * d;      // u_k in the new compact order
     const float *invd = a.ws.invd + (size_t)row * BMAX;
     const int ldo = a.ld_old, ldn = a.ld_new;
-    const int nbp = (nb + 1) & ~1;
+    constexpr int nbp = (nb + 1) & ~1;
     __amdgpu_buffer_rsrc_t rold = __builtin_amdgcn_make_buffer_rsrc(
         (void *)(a.A_old + (size_t)row * a.old_row_stride), 0, d * d * 4, kBufWord3);
     __amdgpu_buffer_rsrc_t rnew = __builtin_amdgcn_make_buffer_rsrc(
@@ -184,7 +189,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         if (k < nb && ii < mn) v = -__fmul_rn(U[(size_t)k * d + ii], invd[k]);
         Fs[k][i] = v;
     }
-    if (tid < FT) rowoff_s[tid] = (i0 + tid < mn) ? map[i0 + tid] * ldo * 4 : kFar;
+    if (tid < FT) {
+        int o = (i0 + tid < mn) ? map[i0 + tid] : -1;
+        rowold_s[tid] = o;
+        rowoff_s[tid] = (o >= 0) ? o * ldo * 4 : kFar;
+    }
 
     // U tile staging: KMAX x 128 floats by 512 threads
     constexpr int UPT = KMAX * FT / 512;
@@ -205,7 +214,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         }
     };
     floatx16 acc[2], nxt[2];
-    auto fetch_c = [&](floatx16(&c)[2], int joldB) {
+    // strictly-lower tiles: element (i, j) sits at old[map i][map j]
+    auto fetch_c = [&](floatx16(&c)[2], int jold) {
+        const int joldB = (jold >= 0) ? jold * 4 : kFar;
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -214,23 +225,38 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                 c[mt][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rold, ro + joldB, 0, 0));
             }
     };
-    auto old_col = [&](int j) { return (j < mn) ? map[j] * 4 : kFar; };
+    // the diagonal tile: entries above the diagonal come from their mirror image
+    auto fetch_c_diag = [&](floatx16(&c)[2], int jold) {
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int oi = rowold_s[wm * 64 + mt * 32 + 8 * (v >> 2) + lrow + (v & 3)];
+                int hi = oi > jold ? oi : jold, lo = oi > jold ? jold : oi;
+                int off = (lo >= 0) ? (hi * ldo + lo) * 4 : kFar;
+                c[mt][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rold, off, 0, 0));
+            }
+    };
+    auto old_col = [&](int j) { return (j < mn) ? map[j] : -1; };
 
-    int joldB = old_col(jl);
-    int joldB_n = old_col(FT + jl);
+    int jold = old_col(jl);
+    int jold_n = old_col(FT + jl);
     fetch_u(0);
-    __syncthreads();                           // rowoff_s visible
-    fetch_c(acc, joldB);
+    __syncthreads();                           // rowoff_s / rowold_s visible
+    if (i0 == 0) fetch_c_diag(acc, jold);
+    else fetch_c(acc, jold);
     stash_u();
-    for (int j0 = 0; j0 < mn; j0 += FT) {
+    for (int j0 = 0; j0 <= i0; j0 += FT) {
         __syncthreads();                       // Us (and, first time, Fs) visible
-        const bool more = j0 + FT < mn;
+        const bool more = j0 + FT <= i0;
         if (more) {
             fetch_u(j0 + FT);
-            fetch_c(nxt, joldB_n);
-            joldB_n = old_col(j0 + 2 * FT + jl);
+            if (j0 + FT == i0) fetch_c_diag(nxt, jold_n);
+            else fetch_c(nxt, jold_n);
+            jold_n = old_col(j0 + 2 * FT + jl);
         }
         const int kl = lane >> 5, il = lane & 31;
+#pragma unroll
         for (int kk = 0; kk < nbp; kk += 2) {
             float a0 = Fs[kk + kl][wm * 64 + il];
             float a1 = Fs[kk + kl][wm * 64 + 32 + il];
@@ -238,7 +264,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
             acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0], 0, 0, 0);
             acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1], 0, 0, 0);
         }
-        const int jcol = j0 + jl;
+    const int jcol = j0 + jl;
         const int lanepart = (jcol < mn) ? (lrow * ldn + jcol) * 4 : kFar;
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
@@ -259,15 +285,15 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 // ------------------------------------------------------------------------------------- host side
 struct Variant {
     int cap;   // largest live size it handles (T * EPT)
-    int B;
-    void (*launch)(int, int, size_t, hipStream_t, const PanelArgs &);
+    int B;     // steps per block
+    int (*launch)(int, int, size_t, hipStream_t, const PanelArgs &);
 };
 
-#define OBC_VARIANT(T, EPT, B) { (T) * (EPT), (B), launch_panel_##T##_##EPT##_##B }
+#define OBC_VARIANT(T, EPT, BR, BL) { (T) * (EPT), (BR) + (BL), launch_panel_##T##_##EPT##_##BR##_##BL }
 
 const Variant kVariants[] = {
-    OBC_VARIANT(256, 1, 64), OBC_VARIANT(1024, 1, 64), OBC_VARIANT(1024, 2, 32),
-    OBC_VARIANT(768, 3, 32), OBC_VARIANT(768, 4, 24),  OBC_VARIANT(768, 6, 16),
+    OBC_VARIANT(256, 1, 64, 0),   OBC_VARIANT(1024, 1, 64, 0), OBC_VARIANT(1024, 2, 32, 16),
+    OBC_VARIANT(768, 3, 32, 16),  OBC_VARIANT(768, 4, 24, 12), OBC_VARIANT(768, 6, 16, 8),
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -335,7 +361,8 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
             const int steps = (host_total - host_done < v->B) ? host_total - host_done : v->B;
             obc_scope sc(ctx, OBC_KERNEL_PANEL, (double)R * steps * 4.0 * m_max,
                          (double)R * steps * (double)steps * m_max);
-            v->launch(mode, R, lds_nm, st, pa);
+            if (v->launch(mode, R, lds_nm, st, pa) != 0)
+                return obc_fail(ctx, OBC_ERR_HIP, "panel kernel: cannot set its dynamic LDS size");
         }
         OBC_LAUNCH_CHECK(ctx, "panel_kernel");
         host_done += v->B;
@@ -351,13 +378,18 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
         fa.strips = (m_next + FT - 1) / FT;
         const int rows8 = (R + 7) / 8 * 8;
         {
-            // the surviving m_next x m_next part of every row's inverse is read and written once
-            obc_scope sc(ctx, OBC_KERNEL_FLUSH, (double)R * 8.0 * m_next * m_next,
-                         (double)R * 2.0 * v->B * (double)m_next * m_next);
-            if (v->B <= 32)
-                flush_kernel<32><<<dim3(fa.strips * rows8), 512, 0, st>>>(fa);
-            else
-                flush_kernel<64><<<dim3(fa.strips * rows8), 512, 0, st>>>(fa);
+            // one triangle of the surviving m_next x m_next part of every row's inverse is read and
+            // written once
+            const double tri = 0.5 * (double)m_next * (m_next + 1.0);   // entries of one triangle
+            obc_scope sc(ctx, OBC_KERNEL_FLUSH, (double)R * 8.0 * tri, (double)R * 2.0 * v->B * tri);
+            const dim3 grid(fa.strips * rows8);
+            switch (v->B) {
+            case 24: flush_kernel<24><<<grid, 512, 0, st>>>(fa); break;
+            case 36: flush_kernel<36><<<grid, 512, 0, st>>>(fa); break;
+            case 48: flush_kernel<48><<<grid, 512, 0, st>>>(fa); break;
+            case 64: flush_kernel<64><<<grid, 512, 0, st>>>(fa); break;
+            default: return obc_fail(ctx, OBC_ERR_BAD_ARG, "row solver: no flush kernel for block size %d", v->B);
+            }
         }
         OBC_LAUNCH_CHECK(ctx, "flush_kernel");
         cur = nxt;
