@@ -7,16 +7,20 @@
 // 1e4..1e5; an fp32 factorisation would already cost three to four digits of H^-1).
 //
 //   1. A = double(H);  blocked right-looking Cholesky A = L L^T with 64-wide block columns:
-//      diagonal block factored (and inverted) inside one workgroup's LDS, the panel below is a
-//      product with the inverted diagonal block, the trailing update is a tiled GEMM.
-//   2. Y = L^-1 by blocked forward substitution (two GEMMs per block row).
+//      the diagonal block is factored and inverted by a single wavefront that keeps it in
+//      registers (lane i owns row i; values move between lanes with v_readlane), the panel below
+//      is a product with the inverted diagonal block, the trailing update is a tiled GEMM.
+//   2. Y = L^-1 by right-looking blocked forward substitution on the identity (two GEMMs per
+//      block row, each over the whole remaining matrix, so all CUs are busy).
 //   3. H^-1 = Y^T Y, lower tiles only, mirrored on store so the result is exactly symmetric.
+// All GEMMs run on the fp64 matrix cores (v_mfma_f64_16x16x4_f64), 64x64 tiles staged through LDS.
 #include "common.h"
 
 namespace {
 
 constexpr int NB = 64;   // block-column width and GEMM tile edge
 constexpr int GK = 16;   // GEMM k-slab
+typedef double doublex4 __attribute__((ext_vector_type(4)));
 
 __global__ void f32_to_f64_kernel(const float *__restrict__ src, double *__restrict__ dst, int64_t n)
 {
@@ -24,63 +28,72 @@ __global__ void f32_to_f64_kernel(const float *__restrict__ src, double *__restr
     if (e < n) dst[e] = (double)src[e];
 }
 
-__global__ void zero_f64_kernel(double *__restrict__ dst, int64_t n)
+__device__ __forceinline__ double readlane_f64(double v, int l)
 {
-    int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e < n) dst[e] = 0.0;
+    long long b = __double_as_longlong(v);
+    unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)b, l);
+    unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)((unsigned long long)b >> 32), l);
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
 }
 
-// Factor the bs x bs diagonal block at A (leading dimension lda) in place (lower triangle), and
-// write the inverse of that triangular factor to Linv (NB x NB, row-major, zeros above the diagonal).
-__global__ __launch_bounds__(256) void potrf_block_kernel(double *__restrict__ A, int lda, int bs,
-                                                          double *__restrict__ Linv, int *status)
+// Factor the bs x bs (bs <= 64) diagonal block at A (leading dimension lda) in place (lower
+// triangle), and write the inverse of that triangular factor to Linv (NB x NB, row-major, zeros
+// above the diagonal).  One wavefront: lane i keeps row i of the block in registers; a block
+// smaller than 64 is padded with the identity.
+__global__ __launch_bounds__(64) void potrf_wave_kernel(double *__restrict__ A, int lda, int bs,
+                                                        double *__restrict__ Linv, int *status)
 {
-    __shared__ double S[NB][NB + 1];
-    __shared__ double T[NB][NB + 1];
-    __shared__ int bad;
-    const int tid = threadIdx.x;
-    if (tid == 0) bad = 0;
-    for (int e = tid; e < NB * NB; e += 256) {
-        int i = e / NB, j = e % NB;
-        S[i][j] = (i < bs && j <= i) ? A[(int64_t)i * lda + j] : 0.0;
-        T[i][j] = 0.0;
+    __shared__ double Ls[NB][NB + 1];
+    const int lane = threadIdx.x;
+    // coalesced load through LDS, then row `lane` into registers
+#pragma unroll 4
+    for (int i = 0; i < NB; ++i) {
+        double v = (i == lane) ? 1.0 : 0.0;
+        if (i < bs && lane <= i) v = A[(int64_t)i * lda + lane];
+        Ls[i][lane] = v;
     }
     __syncthreads();
-    for (int j = 0; j < bs; ++j) {
-        if (tid == 0) {
-            double p = S[j][j];
-            if (!(p > 0.0) || !isfinite(p)) { bad = 1; p = 1.0; }
-            S[j][j] = sqrt(p);
-        }
-        __syncthreads();
-        double ljj = S[j][j];
-        for (int i = j + 1 + tid; i < bs; i += 256) S[i][j] /= ljj;
-        __syncthreads();
-        // trailing update of the lower triangle: S[i][c] -= S[i][j] * S[c][j], j < c <= i
-        int n = bs - j - 1;
-        for (int e = tid; e < n * n; e += 256) {
-            int i = j + 1 + e / n, c = j + 1 + e % n;
-            if (c <= i) S[i][c] -= S[i][j] * S[c][j];
-        }
-        __syncthreads();
-    }
-    // inverse of the triangular block, one column per thread
-    if (tid < bs) {
-        int c = tid;
-        T[c][c] = 1.0 / S[c][c];
-        for (int i = c + 1; i < bs; ++i) {
-            double s = 0.0;
-            for (int k = c; k < i; ++k) s -= S[i][k] * T[k][c];
-            T[i][c] = s / S[i][i];
+    double row[NB];
+#pragma unroll
+    for (int c = 0; c < NB; ++c) row[c] = Ls[lane][c];
+
+    bool bad = false;
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        double pj = readlane_f64(row[j], j);
+        if (!(pj > 0.0) || !(pj < __builtin_inf())) { bad = true; pj = 1.0; }
+        const double ljj = sqrt(pj);
+        const double cj = row[j] / ljj;
+        row[j] = (lane == j) ? ljj : (lane > j ? cj : row[j]);
+        const double mine = (lane > j) ? row[j] : 0.0;     // L[lane][j], 0 on and above the diagonal
+#pragma unroll
+        for (int c = j + 1; c < NB; ++c) {
+            const double lcj = readlane_f64(row[j], c);     // L[c][j]
+            const double f = (lane >= c) ? mine : 0.0;
+            row[c] = fma(-f, lcj, row[c]);
         }
     }
+    // the factor goes to LDS: the inverse below reads it from there (uniform addresses), which
+    // frees the registers that held the rows
     __syncthreads();
-    for (int e = tid; e < NB * NB; e += 256) {
-        int i = e / NB, j = e % NB;
-        if (i < bs && j <= i) A[(int64_t)i * lda + j] = S[i][j];
-        Linv[e] = T[i][j];
+#pragma unroll
+    for (int c = 0; c < NB; ++c) Ls[lane][c] = row[c];
+    __syncthreads();
+    // T = L^-1, lane c computes column c:  T[i][c] = (delta_ic - sum_{k<i} L[i][k] T[k][c]) / L[i][i]
+    double t[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        double acc = (lane == i) ? 1.0 : 0.0;
+#pragma unroll
+        for (int k = 0; k < i; ++k) acc = fma(-Ls[i][k], t[k], acc);
+        t[i] = acc / Ls[i][i];
     }
-    if (tid == 0 && bad) obc_latch(status, OBC_ERR_NOT_SPD);
+#pragma unroll 4
+    for (int i = 0; i < NB; ++i) {
+        if (i < bs && lane <= i) A[(int64_t)i * lda + lane] = Ls[i][lane];
+        Linv[i * NB + lane] = (lane <= i) ? t[i] : 0.0;
+    }
+    if (lane == 0 && bad) obc_latch(status, OBC_ERR_NOT_SPD);
 }
 
 // C (M x N, leading dimension ldc) = alpha * sum_k a(i,k) b(k,j) + beta * C, with
@@ -101,18 +114,19 @@ __global__ __launch_bounds__(256) void gemm64_kernel(int M, int N, int K, double
     __shared__ double As[GK][NB + 1];
     __shared__ double Bs[GK][NB + 1];
     const int tid = threadIdx.x;
-    const int tx = tid & 15, ty = tid >> 4;   // 16 x 16 threads, 4 x 4 outputs each
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;   // 2 x 2 waves, 32 x 32 outputs each (2 x 2 MFMA tiles)
     const int i0 = ti * NB, j0 = tj * NB;
     int kbeg = 0;
     if (klo_mode == 1) kbeg = j0;
     if (klo_mode == 2) kbeg = i0 > j0 ? i0 : j0;
     kbeg = kbeg / GK * GK;
 
-    double acc[4][4];
+    doublex4 acc[2][2];
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) acc[a][b] = 0.0;
+        for (int b = 0; b < 2; ++b) acc[a][b] = doublex4{0.0, 0.0, 0.0, 0.0};
 
     const bool a_kfast = (as_k == 1);
     const bool b_jfast = (bs_j == 1);
@@ -132,49 +146,50 @@ __global__ __launch_bounds__(256) void gemm64_kernel(int M, int N, int K, double
             Bs[kb][j] = u;
         }
         __syncthreads();
+        // v_mfma_f64_16x16x4: lane l supplies a(i = l % 16, k = l / 16) and b(k = l / 16, j = l % 16)
+        const int kl = lane >> 4, il = lane & 15;
 #pragma unroll
-        for (int k = 0; k < GK; ++k) {
-            double a[4], b[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) a[r] = As[k][ty * 4 + r];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) b[c] = Bs[k][tx * 4 + c];
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int c = 0; c < 4; ++c) acc[r][c] = fma(a[r], b[c], acc[r][c]);
+        for (int kk = 0; kk < GK; kk += 4) {
+            double a0 = As[kk + kl][wm * 32 + il];
+            double a1 = As[kk + kl][wm * 32 + 16 + il];
+            double b0 = Bs[kk + kl][wn * 32 + il];
+            double b1 = Bs[kk + kl][wn * 32 + 16 + il];
+            acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
         }
         __syncthreads();
     }
+    // accumulator layout of the fp64 16x16 MFMA: lane holds column (lane % 16) and rows
+    // 4 * r + lane / 16, r = 0..3
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            int i = i0 + ty * 4 + r, j = j0 + tx * 4 + c;
-            if (i >= M || j >= N) continue;
-            if (out32) {
-                float v = (float)(alpha * acc[r][c]);
-                if (ti != tj) {
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                int i = i0 + wm * 32 + mt * 16 + 4 * r + (lane >> 4);
+                int j = j0 + wn * 32 + nt * 16 + (lane & 15);
+                if (i >= M || j >= N) continue;
+                double av = acc[mt][nt][r];
+                if (out32) {
+                    float v = (float)(alpha * av);
                     out32[(int64_t)i * ldc + j] = v;
-                    out32[(int64_t)j * ldc + i] = v;
+                    if (ti != tj) out32[(int64_t)j * ldc + i] = v;
                 } else {
-                    out32[(int64_t)i * ldc + j] = v;
+                    double v = alpha * av;
+                    if (beta != 0.0) v += beta * C[(int64_t)i * ldc + j];
+                    C[(int64_t)i * ldc + j] = v;
                 }
-            } else {
-                double v = alpha * acc[r][c];
-                if (beta != 0.0) v += beta * C[(int64_t)i * ldc + j];
-                C[(int64_t)i * ldc + j] = v;
             }
-        }
 }
 
-// Copy the NB x NB inverse diagonal block into Y's diagonal block.
-__global__ void place_block_kernel(const double *__restrict__ Linv, double *__restrict__ Y, int ldy, int bs)
+// Y = identity (d x d)
+__global__ void eye_f64_kernel(double *__restrict__ dst, int d)
 {
-    for (int e = threadIdx.x; e < NB * NB; e += blockDim.x) {
-        int i = e / NB, j = e % NB;
-        if (i < bs && j < bs) Y[(int64_t)i * ldy + j] = Linv[e];
-    }
+    int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < (int64_t)d * d) dst[e] = (e / d == e % d) ? 1.0 : 0.0;
 }
 
 inline dim3 grid64(int M, int N) { return dim3((N + NB - 1) / NB, (M + NB - 1) / NB); }
@@ -189,8 +204,7 @@ int obc_invert_workspace_bytes(int d, size_t *bytes)
     size_t nblk = (size_t)(d + NB - 1) / NB;
     size_t mat = obc_align_up((size_t)d * d * sizeof(double), 256);
     size_t blocks = obc_align_up(nblk * NB * NB * sizeof(double), 256);
-    size_t tmp = obc_align_up((size_t)NB * d * sizeof(double), 256);
-    *bytes = 2 * mat + blocks + tmp;
+    *bytes = 2 * mat + blocks;
     return OBC_OK;
 }
 
@@ -211,11 +225,10 @@ int obc_invert(obc_ctx *ctx, float *H, int d, void *ws, size_t ws_bytes)
     double *A = (double *)base;
     double *Y = (double *)(base + mat);
     double *Lb = (double *)(base + 2 * mat);
-    double *T = (double *)(base + 2 * mat + obc_align_up((size_t)nblk * NB * NB * sizeof(double), 256));
     const int64_t n = (int64_t)d * d;
 
     f32_to_f64_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(H, A, n);
-    zero_f64_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(Y, n);
+    eye_f64_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(Y, d);
     OBC_LAUNCH_CHECK(ctx, "f32_to_f64_kernel");
 
     // 1. Cholesky, block column by block column
@@ -224,7 +237,7 @@ int obc_invert(obc_ctx *ctx, float *H, int d, void *ws, size_t ws_bytes)
         const int bs = (d - k0 < NB) ? d - k0 : NB;
         double *Akk = A + (int64_t)k0 * d + k0;
         double *Lk = Lb + (int64_t)kb * NB * NB;
-        potrf_block_kernel<<<1, 256, 0, st>>>(Akk, d, bs, Lk, ctx->d_status);
+        potrf_wave_kernel<<<1, 64, 0, st>>>(Akk, d, bs, Lk, ctx->d_status);
         const int m = d - k0 - bs;
         if (m > 0) {
             double *A21 = A + (int64_t)(k0 + bs) * d + k0;
@@ -239,19 +252,21 @@ int obc_invert(obc_ctx *ctx, float *H, int d, void *ws, size_t ws_bytes)
     }
     OBC_LAUNCH_CHECK(ctx, "cholesky kernels");
 
-    // 2. Y = L^-1, block row by block row
-    for (int ib = 0; ib < nblk; ++ib) {
-        const int i0 = ib * NB;
-        const int bs = (d - i0 < NB) ? d - i0 : NB;
-        const double *Li = Lb + (int64_t)ib * NB * NB;
-        place_block_kernel<<<1, 256, 0, st>>>(Li, Y + (int64_t)i0 * d + i0, d, bs);
-        if (i0 > 0) {
-            // T = L[i0.., 0..i0) * Y[0..i0, 0..i0)   (Y lower triangular: k starts at the tile column)
-            gemm64_kernel<<<grid64(bs, i0), 256, 0, st>>>(bs, i0, i0, 1.0, A + (int64_t)i0 * d, d, 1, Y, d, 1,
-                                                           0.0, T, d, 0, 1, nullptr);
-            // Y[i0.., 0..i0) = -Linv_ii * T
-            gemm64_kernel<<<grid64(bs, i0), 256, 0, st>>>(bs, i0, bs, -1.0, Li, NB, 1, T, d, 1, 0.0,
-                                                           Y + (int64_t)i0 * d, d, 0, 0, nullptr);
+    // 2. Y = L^-1: forward substitution on the identity, right-looking.  Before step kb the
+    //    block row kb of Y holds  I_kb - sum_{j<kb} L[kb,j] Y[j]  (only columns < k0 + bs are non-zero).
+    for (int kb = 0; kb < nblk; ++kb) {
+        const int k0 = kb * NB;
+        const int bs = (d - k0 < NB) ? d - k0 : NB;
+        const int nc = k0 + bs;
+        const double *Lk = Lb + (int64_t)kb * NB * NB;
+        double *Yk = Y + (int64_t)k0 * d;
+        // Y[kb] = Linv_kk * Y[kb]   (each workgroup overwrites exactly the columns it has read)
+        gemm64_kernel<<<grid64(bs, nc), 256, 0, st>>>(bs, nc, bs, 1.0, Lk, NB, 1, Yk, d, 1, 0.0, Yk, d, 0, 0, nullptr);
+        const int m = d - k0 - bs;
+        if (m > 0) {
+            // Y[rows below] -= L[rows below, kb] * Y[kb]
+            gemm64_kernel<<<grid64(m, nc), 256, 0, st>>>(m, nc, bs, -1.0, A + (int64_t)(k0 + bs) * d + k0, d, 1,
+                                                          Yk, d, 1, 1.0, Y + (int64_t)(k0 + bs) * d, d, 0, 0, nullptr);
         }
     }
     OBC_LAUNCH_CHECK(ctx, "triangular inverse kernels");
