@@ -99,7 +99,7 @@ __device__ __forceinline__ unsigned long long row16_min_key(unsigned long long k
 struct PanelRow {
     const float *Acur;
     float *gU;
-    int ld, d, m, done, total, ndead, row;
+    int ld, swz, d, m, done, total, ndead, row;
     double qd, qo, qmax, iqd;
     unsigned long long tick;
 };
@@ -162,7 +162,8 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
         int j = tid + e * T;
-        size_t off = (j <= pend) ? (size_t)p * pr.ld + j : (size_t)j * pr.ld + p;
+        const int hi = (j <= pend) ? p : j, lo = (j <= pend) ? j : p;   // element (hi, lo) is kept
+        size_t off = pr.swz ? quad_index(hi, lo, pr.ld) : (size_t)hi * pr.ld + lo;
         col[e] = (j < pr.m) ? pr.Acur[off] : 0.f;
     }
     // the owner of p publishes the pivot's data, the step's scalars and the coefficients
@@ -304,6 +305,7 @@ __global__ __launch_bounds__(T) void panel_kernel(PanelArgs a)
     const int d = a.d, m = pr.m;
     pr.Acur = a.A_cur + (size_t)row * a.a_row_stride;
     pr.ld = a.ld;
+    pr.swz = a.swz;
     pr.gU = a.ws.U + (size_t)row * BMAX * d;
     double *gw = a.ws.w + (size_t)row * d;
     double *gd = a.ws.diag + (size_t)row * d;

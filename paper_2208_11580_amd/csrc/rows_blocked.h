@@ -15,6 +15,16 @@ constexpr int BMAX = 64;       // largest block; leading dimension of the per-ro
 constexpr int FT = 128;        // flush tile edge
 constexpr int FLD = FT + 4;    // padded LDS row of the flush operand tiles
 
+// Layout of a row's private matrix after its first flush ("row-quad" layout): element (i, j) is at
+// float index ((i / 4) * ld + j) * 4 + i % 4, i.e. four consecutive rows of a column sit together.
+// It matches the MFMA accumulator layout (a lane holds four consecutive rows of one column: one
+// 16-byte store) and it makes both ways the panel reads the symmetric matrix -- along a row and
+// along a column -- cost the same 16-byte granularity instead of 4 bytes vs one cache line.
+__host__ __device__ inline size_t quad_index(int i, int j, int ld)
+{
+    return ((size_t)(i >> 2) * ld + j) * 4 + (i & 3);
+}
+
 struct BlockedWs {
     float *Abuf[2];     // R x d x d each
     float *U;           // R x BMAX x d
@@ -37,6 +47,7 @@ struct PanelArgs {
     const float *A_cur;      // matrix buffer the rows are read from
     size_t a_row_stride;     // elements between two rows' matrices (0: all rows share H^-1)
     int ld;                  // leading dimension of A_cur
+    int swz;                 // 0: A_cur is plain row-major (the shared H^-1); 1: row-quad layout
     int d;                   // original width (stride of the per-row state arrays)
     int nm_n, nm_m;
     const float *delta, *offset;

@@ -44,7 +44,7 @@ size_t carve(BlockedWs *ws, void *base, int R, int d)
         off += obc_align_up(bytes, 256);
         return base ? (char *)base + o : (char *)nullptr;
     };
-    size_t mat = (size_t)R * d * d * sizeof(float);
+    size_t mat = (size_t)R * obc_align_up((size_t)d * d, 4) * sizeof(float);
     char *p0 = take(mat), *p1 = take(mat);
     char *pu = take((size_t)R * BMAX * d * sizeof(float));
     char *pi = take((size_t)R * BMAX * sizeof(float));
@@ -122,6 +122,7 @@ struct FlushArgs {
     const float *A_old;
     size_t old_row_stride;   // 0 when every row still reads the shared H^-1
     int ld_old;
+    int old_swz;             // layout of A_old: 0 plain row-major, 1 row-quad (A_new is always row-quad)
     float *A_new;
     size_t new_row_stride;
     int ld_new;
@@ -139,6 +140,7 @@ struct FlushArgs {
 // (register pressure), and the hardware range check (offset >= size reads 0 / drops the store)
 // replaces the per-element predicates.  The loads of the next tile are issued before the MFMAs
 // of the current one.
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 constexpr unsigned kBufWord3 = 0x00020000u;   // raw buffer, 32-bit data format
 constexpr int kFar = 0x40000000;              // byte offset beyond any matrix: "out of range"
 
@@ -171,9 +173,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     const int ldo = a.ld_old, ldn = a.ld_new;
     constexpr int nbp = (nb + 1) & ~1;
     __amdgpu_buffer_rsrc_t rold = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)(a.A_old + (size_t)row * a.old_row_stride), 0, d * d * 4, kBufWord3);
+        (void *)(a.A_old + (size_t)row * a.old_row_stride), 0, (int)(((size_t)d * d + 3) / 4 * 16), kBufWord3);
     __amdgpu_buffer_rsrc_t rnew = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)(a.A_new + (size_t)row * a.new_row_stride), 0, mn * ldn * 4, kBufWord3);
+        (void *)(a.A_new + (size_t)row * a.new_row_stride), 0, ((mn + 3) >> 2) * ldn * 16, kBufWord3);
+    const int swz = a.old_swz;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -192,7 +195,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     if (tid < FT) {
         int o = (i0 + tid < mn) ? map[i0 + tid] : -1;
         rowold_s[tid] = o;
-        rowoff_s[tid] = (o >= 0) ? o * ldo * 4 : kFar;
+        rowoff_s[tid] = (o < 0) ? kFar : swz ? ((o >> 2) * ldo * 4 + (o & 3)) * 4 : o * ldo * 4;
     }
 
     // U tile staging: KMAX x 128 floats by 512 threads
@@ -216,7 +219,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     floatx16 acc[2], nxt[2];
     // strictly-lower tiles: element (i, j) sits at old[map i][map j]
     auto fetch_c = [&](floatx16(&c)[2], int jold) {
-        const int joldB = (jold >= 0) ? jold * 4 : kFar;
+        const int joldB = (jold < 0) ? kFar : swz ? jold * 16 : jold * 4;
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -233,7 +236,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
             for (int v = 0; v < 16; ++v) {
                 int oi = rowold_s[wm * 64 + mt * 32 + 8 * (v >> 2) + lrow + (v & 3)];
                 int hi = oi > jold ? oi : jold, lo = oi > jold ? jold : oi;
-                int off = (lo >= 0) ? (hi * ldo + lo) * 4 : kFar;
+                int off = (lo < 0) ? kFar : swz ? (((hi >> 2) * ldo + lo) * 4 + (hi & 3)) * 4 : (hi * ldo + lo) * 4;
                 c[mt][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rold, off, 0, 0));
             }
     };
@@ -264,14 +267,18 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
             acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0], 0, 0, 0);
             acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1], 0, 0, 0);
         }
-    const int jcol = j0 + jl;
-        const int lanepart = (jcol < mn) ? (lrow * ldn + jcol) * 4 : kFar;
+        // store: a lane's registers 4q .. 4q+3 are four consecutive rows of its column = one
+        // 16-byte slot of the row-quad layout
+        const int jcol = j0 + jl;
+        const int colB = (jcol < mn) ? jcol * 16 : kFar;
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                int rbase = (i0 + wm * 64 + mt * 32 + 8 * (v >> 2) + (v & 3)) * ldn * 4;   // uniform
-                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[mt][v]), rnew, rbase + lanepart, 0, 0);
+            for (int q = 0; q < 4; ++q) {
+                const int quad = (i0 + wm * 64 + mt * 32 + 8 * q + lrow) >> 2;
+                uintx4 v4 = {__float_as_uint(acc[mt][4 * q]), __float_as_uint(acc[mt][4 * q + 1]),
+                             __float_as_uint(acc[mt][4 * q + 2]), __float_as_uint(acc[mt][4 * q + 3])};
+                __builtin_amdgcn_raw_buffer_store_b128(v4, rnew, quad * ldn * 16 + colB, 0, 0);
             }
         __syncthreads();                       // everyone is done reading Us
         if (more) {
@@ -347,6 +354,7 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
 
     const int host_total = (mode == MODE_QUANT) ? d : k_steps;   // upper bound over the rows
     const size_t lds_nm = nm_m > 0 ? obc_align_up((size_t)(d / nm_m), 16) : 0;
+    const size_t mat_stride = obc_align_up((size_t)d * d, 4);   // floats between two rows' matrices
     int host_done = 0;
     int cur = -1;            // -1: the shared H^-1; otherwise index into Abuf
     int ld_cur = d;
@@ -354,8 +362,9 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
         const int m_max = d - host_done;
         const Variant *v = pick_variant(m_max);
         pa.A_cur = (cur < 0) ? Hinv : bw.Abuf[cur];
-        pa.a_row_stride = (cur < 0) ? 0 : (size_t)d * d;
+        pa.a_row_stride = (cur < 0) ? 0 : mat_stride;
         pa.ld = ld_cur;
+        pa.swz = (cur < 0) ? 0 : 1;
         {
             // a panel reads one (corrected) matrix row per step: 4 m bytes, and does ~B m flops on it
             const int steps = (host_total - host_done < v->B) ? host_total - host_done : v->B;
@@ -372,9 +381,10 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
         fa.A_old = pa.A_cur;
         fa.old_row_stride = pa.a_row_stride;
         fa.ld_old = ld_cur;
+        fa.old_swz = pa.swz;
         fa.A_new = bw.Abuf[nxt];
-        fa.new_row_stride = (size_t)d * d;
-        fa.ld_new = (m_next + 3) & ~3;
+        fa.new_row_stride = mat_stride;
+        fa.ld_new = m_next;
         fa.strips = (m_next + FT - 1) / FT;
         const int rows8 = (R + 7) / 8 * 8;
         {
