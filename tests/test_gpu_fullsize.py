@@ -60,3 +60,102 @@ def test_conv256x2304_obq4_sampled_rows(obc, orc):
     assert torch.all(q_obq < q_rtn)
     # the loss trace sums to that quadratic form (loss identity) on every row
     assert torch.allclose(res["loss"].double().sum(dim=1), 0.5 * q_obq, rtol=2e-3)
+
+
+def test_ffn768x3072_prune_sampled_row(obc, orc):
+    """The second target layer (d_col = 3072): whole layer on the GPU with the HBM trace, global
+    step to 50 %, weights gathered from the trace; the oracle replays one sampled row."""
+    W, X, _ = obc_inputs.make_layer("ffn768x3072", device="cuda")
+    R, d = W.shape
+    H = obc.obc_hessian(X)
+    Hinv = obc.obc_invert(H)
+    res = obc.obc_prune_rows(W, Hinv, want_trace=True)
+    obc.obc_check()
+    k = obc_inputs.target_count(0.5, R, d)
+    counts, mask = obc.obc_global_select(res["loss"], res["order"], k)
+    What = obc.obc_gather_trace(W, res["trace"], counts)
+    torch.cuda.synchronize()
+    assert int(counts.sum()) == k and int(mask.sum()) == k
+    # the mask is exactly the zero pattern of the gathered weights
+    assert torch.equal(What == 0, mask.bool())
+    # every row's order is a permutation; cumulative loss is non-decreasing
+    srt = torch.sort(res["order"], dim=1).values
+    assert torch.equal(srt, torch.arange(d, device="cuda", dtype=torch.int32).expand(R, d))
+    assert torch.all(res["loss"] >= 0)
+    # Algorithm 2 property: every pruned weight's key (prefix max of its row's losses) is <= every
+    # kept weight's key
+    keys = torch.cummax(res["loss"], dim=1).values
+    idx = torch.arange(d, device="cuda").expand(R, d)
+    pruned = idx < counts[:, None]
+    assert keys[pruned].max() <= keys[~pruned].min()
+    # one sampled row against the oracle, including its state at the count the global step chose
+    i = 77
+    st = RowParity()
+    A = _np(Hinv)
+    r = check_row(orc, st, "prune", A, _np(W[i]), _np(res["order"][i]), _np(res["loss"][i]),
+                  _np(res["W"][i]), d)
+    print(st)
+    c = int(counts[i])
+    ref = orc.prune_row(A.astype(np.float64), _np(W[i]).astype(np.float64), k_steps=c,
+                        forced=_np(res["order"][i]).astype(np.int32)).w
+    got = _np(What[i]).astype(np.float64)
+    assert np.linalg.norm(got - ref) <= 1e-4 * np.linalg.norm(ref)
+
+
+def test_conv64x576_end_to_end_layer_error(obc, orc):
+    """configs[1] at full size: Hessian, inverse, pruning traces, global step to 60 %, and 2:4, all
+    on the GPU; the oracle runs its own whole path from X in fp64.  Graded on the layer error."""
+    W, X, _ = obc_inputs.make_layer("conv64x576", device="cuda")
+    R, d = W.shape
+    Hinv = obc.obc_invert(obc.obc_hessian(X))
+    res = obc.obc_prune_rows(W, Hinv, want_trace=True)
+    k = obc_inputs.target_count(0.6, R, d)
+    counts, mask = obc.obc_global_select(res["loss"], res["order"], k)
+    What = obc.obc_gather_trace(W, res["trace"], counts)
+    nm = obc.obc_prune_rows(W, Hinv, nm=(2, 4))
+    obc.obc_check()
+    Xn, Wn = _np(X), _np(W).astype(np.float64)
+    Ho = orc.hessian(Xn)
+    Ao = orc.invert(Ho)
+    assert np.linalg.norm(_np(Hinv) - Ao) / np.linalg.norm(Ao) < 1e-4
+    ro = orc.prune_rows(Ao, Wn, n_threads=16)
+    co = orc.global_select(ro["loss"], k)
+    Wo = orc.reconstruct(Ao, Wn, co)
+    # counts may differ by near-ties between the fp32 and fp64 inverses; the layer error may not
+    assert np.abs(_np(counts) - co).sum() <= 0.002 * k
+    Hq = Ho - 0.0  # (w-w^)^T H (w-w^) / 2 with the damped H = ||.X||^2 + lambda/2 ||.||^2
+    def quad(Wh):
+        E = Wn - Wh
+        return 0.5 * float(np.sum((E @ Hq) * E))
+    e_gpu, e_orc = quad(_np(What).astype(np.float64)), quad(Wo)
+    assert abs(e_gpu - e_orc) <= 1e-3 * e_orc, (e_gpu, e_orc)
+    no = orc.prune_rows(Ao, Wn, nm=(2, 4), n_threads=16)
+    e_gpu, e_orc = quad(_np(nm["W"]).astype(np.float64)), quad(no["W"])
+    assert abs(e_gpu - e_orc) <= 1e-3 * e_orc, (e_gpu, e_orc)
+    zeros = (_np(nm["W"]) == 0).reshape(R, -1, 4).sum(axis=2)
+    assert np.all(zeros == 2)
+
+
+def test_compound_prune_then_quantize(obc, orc):
+    """configs[4]'s recipe at a size the oracle finishes: global pruning to 50 %, then OBQ 4-bit on
+    the survivors (dense sub-problem per row), GPU vs oracle row by row."""
+    W, X, _ = obc_inputs.make_layer("conv512x4608", device="cuda", d_row=6, d_col=448, n_samples=4000)
+    R, d = W.shape
+    Hinv = obc.obc_invert(obc.obc_hessian(X))
+    res = obc.obc_prune_rows(W, Hinv, want_trace=True)
+    k = obc_inputs.target_count(0.5, R, d)
+    counts, mask = obc.obc_global_select(res["loss"], res["order"], k)
+    Wp = obc.obc_gather_trace(W, res["trace"], counts)
+    live = (1 - mask).contiguous()
+    delta, offset, maxq = obc.obc_minmax_grid(Wp, 4, live=live)
+    q = obc.obc_quant_rows(Wp, Hinv, delta, offset, maxq, live=live)
+    obc.obc_check()
+    st = RowParity()
+    A = _np(Hinv)
+    for i in range(R):
+        n_live = int(live[i].sum())
+        check_row(orc, st, "quant", A, _np(Wp[i]), _np(q["order"][i]), _np(q["loss"][i]), _np(q["W"][i]),
+                  n_live, grid=(float(delta[i]), float(offset[i]), maxq), g_codes=_np(q["codes"][i]),
+                  live=_np(live[i]))
+    print(st)
+    assert torch.all(q["W"][mask.bool()] == 0) and torch.all(q["codes"][mask.bool()] == -1)
