@@ -299,7 +299,7 @@ struct Variant {
 #define OBC_VARIANT(T, EPT, BR, BL) { (T) * (EPT), (BR) + (BL), launch_panel_##T##_##EPT##_##BR##_##BL }
 
 const Variant kVariants[] = {
-    OBC_VARIANT(256, 1, 64, 0),   OBC_VARIANT(1024, 1, 64, 0), OBC_VARIANT(1024, 2, 32, 16),
+    OBC_VARIANT(256, 1, 64, 0),   OBC_VARIANT(1024, 1, 64, 0), OBC_VARIANT(512, 4, 40, 16),
     OBC_VARIANT(768, 3, 32, 16),  OBC_VARIANT(768, 4, 24, 12), OBC_VARIANT(768, 6, 16, 8),
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
@@ -396,6 +396,7 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
             switch (v->B) {
             case 24: flush_kernel<24><<<grid, 512, 0, st>>>(fa); break;
             case 36: flush_kernel<36><<<grid, 512, 0, st>>>(fa); break;
+            case 56: flush_kernel<56><<<grid, 512, 0, st>>>(fa); break;
             case 48: flush_kernel<48><<<grid, 512, 0, st>>>(fa); break;
             case 64: flush_kernel<64><<<grid, 512, 0, st>>>(fa); break;
             default: return obc_fail(ctx, OBC_ERR_BAD_ARG, "row solver: no flush kernel for block size %d", v->B);
