@@ -154,15 +154,14 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
     if (key == ~0ull) return 2;
     const int p = (int)(unsigned)key;
 
-    // ---- (2) fetch the owned part of row p of A0.  Only the tiles on and below the block
-    // diagonal of A0 are kept up to date (the matrix is symmetric): up to the end of p's
-    // 128-wide tile the row itself is read, beyond it column p.
+    // ---- (2) fetch the owned part of row p of A0.  Only the lower triangle of A0 is kept up to
+    // date (the matrix is symmetric): entry (p, j) is read as (max(p, j), min(p, j)), i.e. along
+    // row p up to the diagonal and down column p below it.
     float col[EPT];
-    const int pend = p | (FT - 1);
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
         int j = tid + e * T;
-        const int hi = (j <= pend) ? p : j, lo = (j <= pend) ? j : p;   // element (hi, lo) is kept
+        const int hi = (j <= p) ? p : j, lo = (j <= p) ? j : p;
         size_t off = pr.swz ? quad_index(hi, lo, pr.ld) : (size_t)hi * pr.ld + lo;
         col[e] = (j < pr.m) ? pr.Acur[off] : 0.f;
     }

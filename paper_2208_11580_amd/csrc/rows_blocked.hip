@@ -131,9 +131,9 @@ struct FlushArgs {
 };
 
 // One workgroup (8 waves) per 128-row strip of one row's matrix; it walks the strip's 128-column
-// tiles up to and including the diagonal one: the matrix is symmetric, so only the tiles on and
-// below the block diagonal are kept (the panel reads row p as "row part + column part").  A
-// diagonal tile is written in full; its upper-triangle entries are read from their mirror images.  Wave (wm, wn) owns a 64 x 32 sub-tile = two 32x32 MFMA accumulators, which are loaded
+// tiles up to and including the diagonal one: the matrix is symmetric, so only its lower triangle
+// is kept (the panel reads row p as "row part + column part").  In a diagonal tile the entries
+// above the diagonal are neither read nor (except as don't-care slots of a 4-row store) written.  Wave (wm, wn) owns a 64 x 32 sub-tile = two 32x32 MFMA accumulators, which are loaded
 // straight from the old matrix (one dword per lane: 32 consecutive columns of a row per half
 // wave, i.e. whole 128-byte lines) and stored straight to the new one.  Accesses to the matrices
 // are raw buffer loads / stores: a 32-bit byte offset per access instead of a 64-bit address
@@ -228,15 +228,15 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                 c[mt][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rold, ro + joldB, 0, 0));
             }
     };
-    // the diagonal tile: entries above the diagonal come from their mirror image
+    // the diagonal tile: only entries on or below the diagonal exist
     auto fetch_c_diag = [&](floatx16(&c)[2], int jold) {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 int oi = rowold_s[wm * 64 + mt * 32 + 8 * (v >> 2) + lrow + (v & 3)];
-                int hi = oi > jold ? oi : jold, lo = oi > jold ? jold : oi;
-                int off = (lo < 0) ? kFar : swz ? (((hi >> 2) * ldo + lo) * 4 + (hi & 3)) * 4 : (hi * ldo + lo) * 4;
+                int off = (jold < 0 || jold > oi) ? kFar
+                          : swz ? (((oi >> 2) * ldo + jold) * 4 + (oi & 3)) * 4 : (oi * ldo + jold) * 4;
                 c[mt][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rold, off, 0, 0));
             }
     };
@@ -275,7 +275,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int quad = (i0 + wm * 64 + mt * 32 + 8 * q + lrow) >> 2;
+                const int qrow = i0 + wm * 64 + mt * 32 + 8 * q + lrow;   // first row of the quad
+                const int quad = qrow >> 2;
+                if (j0 == i0 && jcol > qrow + 3) continue;                  // wholly above the diagonal
                 uintx4 v4 = {__float_as_uint(acc[mt][4 * q]), __float_as_uint(acc[mt][4 * q + 1]),
                              __float_as_uint(acc[mt][4 * q + 2]), __float_as_uint(acc[mt][4 * q + 3])};
                 __builtin_amdgcn_raw_buffer_store_b128(v4, rnew, quad * ldn * 16 + colB, 0, 0);
