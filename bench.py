@@ -165,6 +165,13 @@ def main():
     else:
         roofline = {"bound": "hbm", "kernel": names[dom], "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": gbs / HBM_PEAK_GBS, "traffic": None}
+    # measured HBM bytes per launch of the dominant kernel, from the stored rocprofv3 counter runs of
+    # this same command (profiles/hbm_traffic_<workload>.txt), when such a summary exists
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % args.workload.replace("-", "_"))
+    if os.path.exists(tpath) and args.strategy == "auto":
+        for ln in open(tpath):
+            if ln.startswith("family %s " % names[dom]):
+                roofline["traffic"] = float(ln.split("traffic_bytes_per_launch=")[1].split()[0])
     roofline.update({
         "launches_per_step": ds["launches"] / args.steps, "avg_launch_ms": per_launch_ms,
         "alg_bytes_per_launch": ds["bytes"] / ds["launches"], "mfma_tflops": tfs,

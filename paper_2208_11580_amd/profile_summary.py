@@ -66,13 +66,22 @@ def traffic(fetch_csv, write_csv, workload, command):
     print("calibration: the plain 1 GiB copy reads FETCH_SIZE = %.0f KiB, WRITE_SIZE = %.0f KiB" % (f[copy][3], w[copy][3]))
     print("             -> scale factors %.3f (fetch), %.3f (write)" % (fscale, wscale))
     print("%-34s %7s %14s %14s %14s %9s" % ("kernel", "launches", "fetch GB", "write GB", "bytes/launch", "ms total"))
+    fam = collections.OrderedDict()
     for k in f:
-        if not any(t in k for t in ("flush_kernel", "panel_kernel", "rows_rank1_kernel")):
+        family = next((t for t in ("flush_kernel", "panel_kernel", "rows_rank1_kernel") if t in k), None)
+        if family is None:
             continue
         fb = f[k][1] * 1024.0 * fscale
         wb = w.get(k, [0, 0.0])[1] * 1024.0 * wscale
         print("%-34s %7d %14.3f %14.3f %14.0f %9.3f" % (k[:34], f[k][0], fb / 1e9, wb / 1e9, (fb + wb) / f[k][0], f[k][2]))
-        print("traffic_bytes_per_launch[%s]=%.0f" % (k.split("<")[0] + ("<" + k.split("<")[1] if "<" in k else ""), (fb + wb) / f[k][0]))
+        a = fam.setdefault(family, [0, 0.0, 0.0])
+        a[0] += f[k][0]
+        a[1] += fb + wb
+        a[2] += f[k][2]
+    print("per kernel family (all template variants together):")
+    for family, a in fam.items():
+        print("family %s launches=%d traffic_bytes_per_launch=%.0f hbm_GBps=%.1f" % (
+            family, a[0], a[1] / a[0], a[1] / (a[2] * 1e-3) / 1e9))
 
 
 if __name__ == "__main__":

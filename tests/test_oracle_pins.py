@@ -465,3 +465,25 @@ def test_rows_driver_equals_single_rows_and_is_deterministic(orc):
     for i in range(R):
         r = orc.quant_row(A, W[i], grids[i])
         assert np.array_equal(q["codes"][i], r.codes) and np.array_equal(q["W"][i], r.w)
+
+
+# ----------------------------------------------------------------------------- regression fixture
+def test_oracle_reproduces_its_golden_fixture(orc):
+    """tests/golden/tiny_layer.json (written by make_golden.py from the oracle alone) still holds."""
+    import json
+    import os
+
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "tiny_layer.json")))
+    X, W = np.array(g["X"]), np.array(g["W"])
+    A = orc.invert(orc.hessian(X, damp_rel=g["damp_rel"]))
+    pr = orc.prune_rows(A, W)
+    assert pr["order"].tolist() == g["prune_order"]
+    assert np.allclose(pr["loss"], g["prune_loss"], rtol=1e-10)
+    counts = orc.global_select(pr["loss"], g["k"])
+    assert counts.tolist() == g["counts"]
+    assert np.allclose(orc.reconstruct(A, W, counts), g["W_pruned"], rtol=1e-10, atol=1e-15)
+    grids = [orc.minmax_grid(W[i], g["bits"]) for i in range(g["R"])]
+    q = orc.quant_rows(A, W, [x[0] for x in grids], [x[1] for x in grids], (1 << g["bits"]) - 1)
+    assert q["codes"].tolist() == g["quant_codes"] and q["order"].tolist() == g["quant_order"]
+    nm = orc.prune_rows(A, W, nm=(2, 4))
+    assert nm["order"].tolist() == g["nm24_order"]
