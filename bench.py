@@ -31,6 +31,7 @@ WORKLOADS = {
     "ffn3072x768-prune50": ("ffn3072x768", "prune50"),
     "ffn3072x768-obq4": ("ffn3072x768", "obq4"),
     "conv512x4608-prune50": ("conv512x4608", "prune50"),
+    "conv512x4608-compound": ("conv512x4608", "compound50"),   # prune to 50 %, then OBQ 4-bit on survivors
     "lin16x32-prune50": ("lin16x32", "prune50"),
 }
 DEFAULT_WORKLOAD = "conv256x2304-obq4"
@@ -70,14 +71,16 @@ def main():
     N = X.shape[1]
     ctx = pkg.Context()
 
-    if task.startswith("prune"):
-        sparsity = int(task[5:]) / 100.0
+    if task.startswith("prune") or task.startswith("compound"):
+        sparsity = int(task[-2:]) / 100.0
         k_steps, nm = d, (0, 0)
     elif task == "nm24":
         k_steps, nm = d // 2, (2, 4)
     else:
         k_steps, nm = d, (0, 0)
     row_steps = R * k_steps
+    if task.startswith("compound"):
+        row_steps += R * d      # second pass: eliminations of the pruned + OBQ steps of the survivors
 
     # outputs allocated once (device memory is the caller's business, outside the timed path)
     H = torch.empty(d, d, device="cuda")
@@ -86,7 +89,11 @@ def main():
                W=torch.empty(R, d, device="cuda"))
     if task.startswith("obq"):
         out["codes"] = torch.empty(R, d, dtype=torch.int32, device="cuda")
-    want_trace = task.startswith("prune")
+    qout = None
+    if task.startswith("compound"):
+        qout = dict(order=torch.empty(R, d, dtype=torch.int32, device="cuda"), loss=torch.empty(R, d, device="cuda"),
+                    W=torch.empty(R, d, device="cuda"), codes=torch.empty(R, d, dtype=torch.int32, device="cuda"))
+    want_trace = task.startswith("prune") or task.startswith("compound")
     trace_bytes = R * k_steps * d * 4
     if want_trace and trace_bytes > 120e9:
         want_trace = False        # largest layers: recover by replay instead of the HBM trace
@@ -113,13 +120,17 @@ def main():
                                      strategy=strategy, out=out)
         e[3].record()
         result = res["W"]
-        if task.startswith("prune"):
+        if task.startswith("prune") or task.startswith("compound"):
             k = obc_inputs.target_count(sparsity, R, d)
             counts, mask = ctx.obc_global_select(res["loss"], res["order"], k)
             if want_trace:
                 result = ctx.obc_gather_trace(W, res["trace"], counts)
             else:
                 result = ctx.obc_prune_rows(W, H, k_steps=k_steps, stop_counts=counts, strategy=strategy)["W"]
+            if task.startswith("compound"):
+                live = 1 - mask
+                delta, offset, maxq = ctx.obc_minmax_grid(result, 4, live=live)
+                result = ctx.obc_quant_rows(result, H, delta, offset, maxq, live=live, strategy=strategy, out=qout)["W"]
         e[4].record()
         if record:
             torch.cuda.synchronize()

@@ -67,6 +67,7 @@ struct PanelArgs {
 #define OBC_DECLARE_PANEL(T, EPT, BR, BL) \
     int launch_panel_##T##_##EPT##_##BR##_##BL(int mode, int R, size_t lds_nm, hipStream_t st, const PanelArgs &a)
 OBC_DECLARE_PANEL(256, 1, 64, 0);
+OBC_DECLARE_PANEL(256, 3, 32, 16);
 OBC_DECLARE_PANEL(1024, 1, 64, 0);
 OBC_DECLARE_PANEL(512, 4, 40, 16);
 OBC_DECLARE_PANEL(768, 3, 32, 16);

@@ -306,3 +306,17 @@ def test_argument_errors(obc):
     # empty inputs are fine
     out = obc.obc_prune_rows(W[:0], Hinv)
     assert out["order"].shape == (0, 30)
+
+
+def test_rows_many_more_rows_than_cus(obc, orc):
+    """Several times more rows than CUs at a mid-size width: the solver switches to the panel variant
+    of which three workgroups share a CU; sampled rows against the oracle, all rows against invariants."""
+    R, d = 1030, 420
+    W, X = _layer("attn768x768", d_col=d, d_row=R, n_samples=2000)
+    Hinv = _hinv(obc, X)
+    rows = [0, 515, 1029]
+    res, _ = _check_prune(obc, orc, W, Hinv, d, (0, 0), 2, rows=rows)
+    srt = torch.sort(res["order"], dim=1).values
+    assert torch.equal(srt, torch.arange(d, device="cuda", dtype=torch.int32).expand(R, d))
+    assert torch.all(res["W"] == 0)
+    _check_quant(obc, orc, W, Hinv, 4, 2, rows=rows)
