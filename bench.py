@@ -102,7 +102,6 @@ def main():
     ctx.workspace(max(ctx.rows_workspace_bytes(R, d, strategy), 1 << 20))
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    rows_ms = []
     stage_ms = {"hessian": [], "invert": [], "rows": [], "global": []}
 
     def one_step(record):

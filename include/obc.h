@@ -42,8 +42,10 @@ extern "C" {
 #define OBC_ERR_NUMERIC (-5)   /* a row solver met a non-positive / non-finite [H^-1]_pp */
 #define OBC_ERR_HIP (-6)       /* a HIP runtime call failed */
 
-/* Row-solver strategies (argument `strategy` below).  AUTO picks LDS-resident rank-1 for
- * small d_col and the blocked solver otherwise. */
+/* Row-solver strategies (argument `strategy` below).  AUTO picks the rank-1 solver with the
+ * row's matrix resident in LDS for d_col <= 192, the blocked solver up to d_col = 4608 and the
+ * streamed rank-1 solver beyond (as far as its per-row vectors fit in LDS, d_col <= ~5600;
+ * larger d_col returns OBC_ERR_BAD_SHAPE). */
 #define OBC_STRATEGY_AUTO 0
 #define OBC_STRATEGY_RANK1 1   /* literal Algorithm 1: one rank-1 elimination per step */
 #define OBC_STRATEGY_BLOCKED 2 /* same arithmetic result, eliminations applied in blocks */

@@ -134,7 +134,7 @@ class Context:
         nbytes = max(int(nbytes), 256)
         if self._ws is None or self._ws.numel() < nbytes:
             self._ws = None
-            self._ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+            self._ws = torch.empty(nbytes, dtype=torch.uint8, device=torch.device("cuda", torch.cuda.current_device()))
         return self._ws
 
     def release_workspace(self):

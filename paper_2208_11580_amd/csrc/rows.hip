@@ -10,6 +10,7 @@ int rank1_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, int 
                  const float *offset, int maxq, const uint8_t *live, int32_t *order, float *loss,
                  int32_t *codes, float *W_out, float *trace, int out_ld, void *ws, size_t ws_bytes);
 size_t blocked_workspace_bytes(int R, int d);
+int blocked_max_d();
 int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, int R, int d, int k_steps,
                    int nm_n, int nm_m, const int32_t *stop_counts, const float *delta,
                    const float *offset, int maxq, const uint8_t *live, int32_t *order, float *loss,
@@ -23,7 +24,8 @@ using namespace obc_rows;
 int pick_strategy(int strategy, int d)
 {
     if (strategy == OBC_STRATEGY_RANK1 || strategy == OBC_STRATEGY_BLOCKED) return strategy;
-    return rank1_lds_resident(d, 8) ? OBC_STRATEGY_RANK1 : OBC_STRATEGY_BLOCKED;
+    if (rank1_lds_resident(d, 8)) return OBC_STRATEGY_RANK1;
+    return d <= blocked_max_d() ? OBC_STRATEGY_BLOCKED : OBC_STRATEGY_RANK1;
 }
 
 // offset = min, delta = (max - min) / maxq over the live weights of each row; one wave per row.
