@@ -103,13 +103,30 @@ __global__ __launch_bounds__(64) void potrf_wave_kernel(double *__restrict__ A, 
 //                2 = at max(first row, first column) (a^T and b lower triangular)
 //   out32      : nullable; when given the result is rounded to fp32 there (leading dimension
 //                ldc) and mirrored across the diagonal instead of being written to C
-__global__ __launch_bounds__(256) void gemm64_kernel(int M, int N, int K, double alpha,
-                                                     const double *A, int64_t as_i, int64_t as_k,
-                                                     const double *B, int64_t bs_k, int64_t bs_j,
-                                                     double beta, double *C, int64_t ldc,
-                                                     int lower_only, int klo_mode, float *out32)
+struct GemmArgs {
+    int M, N, K;
+    double alpha;
+    const double *A;
+    int64_t as_i, as_k;
+    const double *B;
+    int64_t bs_k, bs_j;
+    double beta;
+    double *C;
+    int64_t ldc;
+    int lower_only, klo_mode;
+    float *out32;
+};
+
+__device__ __forceinline__ void gemm64_tile(const GemmArgs &g, int ti, int tj)
 {
-    const int ti = blockIdx.y, tj = blockIdx.x;
+    const int M = g.M, N = g.N, K = g.K;
+    const double alpha = g.alpha, beta = g.beta;
+    const double *A = g.A, *B = g.B;
+    double *C = g.C;
+    const int64_t as_i = g.as_i, as_k = g.as_k, bs_k = g.bs_k, bs_j = g.bs_j, ldc = g.ldc;
+    const int lower_only = g.lower_only, klo_mode = g.klo_mode;
+    float *out32 = g.out32;
+    if (ti * NB >= M || tj * NB >= N) return;
     if (lower_only && tj > ti) return;
     __shared__ double As[GK][NB + 1];
     __shared__ double Bs[GK][NB + 1];
@@ -185,6 +202,16 @@ __global__ __launch_bounds__(256) void gemm64_kernel(int M, int N, int K, double
             }
 }
 
+__global__ __launch_bounds__(256) void gemm64_kernel(GemmArgs g) { gemm64_tile(g, blockIdx.y, blockIdx.x); }
+
+// Two independent products in one launch (blockIdx.z picks the problem): the small products of a
+// factorisation step are latency-bound, so pairing them halves the number of launches.
+__global__ __launch_bounds__(256) void gemm64_dual_kernel(GemmArgs g0, GemmArgs g1)
+{
+    if (blockIdx.z == 0) gemm64_tile(g0, blockIdx.y, blockIdx.x);
+    else gemm64_tile(g1, blockIdx.y, blockIdx.x);
+}
+
 // Y = identity (d x d)
 __global__ void eye_f64_kernel(double *__restrict__ dst, int d)
 {
@@ -231,48 +258,54 @@ int obc_invert(obc_ctx *ctx, float *H, int d, void *ws, size_t ws_bytes)
     eye_f64_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(Y, d);
     OBC_LAUNCH_CHECK(ctx, "f32_to_f64_kernel");
 
-    // 1. Cholesky, block column by block column
-    for (int kb = 0; kb < nblk; ++kb) {
-        const int k0 = kb * NB;
-        const int bs = (d - k0 < NB) ? d - k0 : NB;
-        double *Akk = A + (int64_t)k0 * d + k0;
-        double *Lk = Lb + (int64_t)kb * NB * NB;
-        potrf_wave_kernel<<<1, 64, 0, st>>>(Akk, d, bs, Lk, ctx->d_status);
-        const int m = d - k0 - bs;
-        if (m > 0) {
-            double *A21 = A + (int64_t)(k0 + bs) * d + k0;
-            // L21 = A21 * Linv_kk^T  (each workgroup overwrites exactly the rows it has read)
-            gemm64_kernel<<<grid64(m, bs), 256, 0, st>>>(m, bs, bs, 1.0, A21, d, 1, Lk, 1, NB, 0.0,
-                                                          A21, d, 0, 0, nullptr);
-            // A22 -= L21 L21^T on the lower tiles
-            double *A22 = A + (int64_t)(k0 + bs) * d + (k0 + bs);
-            gemm64_kernel<<<grid64(m, m), 256, 0, st>>>(m, m, bs, -1.0, A21, d, 1, A21, 1, d, 1.0,
-                                                         A22, d, 1, 0, nullptr);
-        }
-    }
-    OBC_LAUNCH_CHECK(ctx, "cholesky kernels");
+    auto mk = [](int M, int N, int K, double alpha, const double *A, int64_t as_i, int64_t as_k,
+                 const double *B, int64_t bs_k, int64_t bs_j, double beta, double *C, int64_t ldc,
+                 int lower_only, int klo_mode, float *out32) {
+        GemmArgs g;
+        g.M = M; g.N = N; g.K = K; g.alpha = alpha; g.A = A; g.as_i = as_i; g.as_k = as_k; g.B = B;
+        g.bs_k = bs_k; g.bs_j = bs_j; g.beta = beta; g.C = C; g.ldc = ldc; g.lower_only = lower_only;
+        g.klo_mode = klo_mode; g.out32 = out32;
+        return g;
+    };
+    auto dual_grid = [](const GemmArgs &a, const GemmArgs &b) {
+        unsigned gx = (unsigned)((((a.N > b.N) ? a.N : b.N) + NB - 1) / NB);
+        unsigned gy = (unsigned)((((a.M > b.M) ? a.M : b.M) + NB - 1) / NB);
+        return dim3(gx, gy, 2);
+    };
 
-    // 2. Y = L^-1: forward substitution on the identity, right-looking.  Before step kb the
-    //    block row kb of Y holds  I_kb - sum_{j<kb} L[kb,j] Y[j]  (only columns < k0 + bs are non-zero).
+    // 1 + 2. Cholesky A = L L^T and Y = L^-1 together, block column by block column.  Step kb:
+    //   potrf:    L_kk and its inverse
+    //   launch A: L21 = A21 Linv_kk^T   |  Y[kb] = Linv_kk Y[kb]
+    //   launch B: A22 -= L21 L21^T (lower tiles)  |  Y[rows below] -= L21 Y[kb]
+    // (Y starts as the identity: forward substitution on the identity, right-looking; before step
+    // kb its block row kb holds I_kb - sum_{j<kb} L[kb,j] Y[j], non-zero only in columns < k0 + bs.)
     for (int kb = 0; kb < nblk; ++kb) {
         const int k0 = kb * NB;
         const int bs = (d - k0 < NB) ? d - k0 : NB;
         const int nc = k0 + bs;
-        const double *Lk = Lb + (int64_t)kb * NB * NB;
-        double *Yk = Y + (int64_t)k0 * d;
-        // Y[kb] = Linv_kk * Y[kb]   (each workgroup overwrites exactly the columns it has read)
-        gemm64_kernel<<<grid64(bs, nc), 256, 0, st>>>(bs, nc, bs, 1.0, Lk, NB, 1, Yk, d, 1, 0.0, Yk, d, 0, 0, nullptr);
         const int m = d - k0 - bs;
+        double *Akk = A + (int64_t)k0 * d + k0;
+        double *Lk = Lb + (int64_t)kb * NB * NB;
+        double *Yk = Y + (int64_t)k0 * d;
+        potrf_wave_kernel<<<1, 64, 0, st>>>(Akk, d, bs, Lk, ctx->d_status);
+        // each workgroup overwrites exactly the rows / columns it has read
+        GemmArgs trsm_row = mk(bs, nc, bs, 1.0, Lk, NB, 1, Yk, d, 1, 0.0, Yk, d, 0, 0, nullptr);
         if (m > 0) {
-            // Y[rows below] -= L[rows below, kb] * Y[kb]
-            gemm64_kernel<<<grid64(m, nc), 256, 0, st>>>(m, nc, bs, -1.0, A + (int64_t)(k0 + bs) * d + k0, d, 1,
-                                                          Yk, d, 1, 1.0, Y + (int64_t)(k0 + bs) * d, d, 0, 0, nullptr);
+            double *A21 = A + (int64_t)(k0 + bs) * d + k0;
+            double *A22 = A + (int64_t)(k0 + bs) * d + (k0 + bs);
+            GemmArgs panel = mk(m, bs, bs, 1.0, A21, d, 1, Lk, 1, NB, 0.0, A21, d, 0, 0, nullptr);
+            gemm64_dual_kernel<<<dual_grid(panel, trsm_row), 256, 0, st>>>(panel, trsm_row);
+            GemmArgs trail = mk(m, m, bs, -1.0, A21, d, 1, A21, 1, d, 1.0, A22, d, 1, 0, nullptr);
+            GemmArgs trsm_upd = mk(m, nc, bs, -1.0, A21, d, 1, Yk, d, 1, 1.0, Y + (int64_t)(k0 + bs) * d, d, 0, 0, nullptr);
+            gemm64_dual_kernel<<<dual_grid(trail, trsm_upd), 256, 0, st>>>(trail, trsm_upd);
+        } else {
+            gemm64_kernel<<<grid64(bs, nc), 256, 0, st>>>(trsm_row);
         }
     }
-    OBC_LAUNCH_CHECK(ctx, "triangular inverse kernels");
+    OBC_LAUNCH_CHECK(ctx, "factorisation kernels");
 
     // 3. H^-1 = Y^T Y, rounded to fp32, mirrored
-    gemm64_kernel<<<grid64(d, d), 256, 0, st>>>(d, d, d, 1.0, Y, 1, d, Y, d, 1, 0.0, nullptr, d, 1, 2, H);
+    gemm64_kernel<<<grid64(d, d), 256, 0, st>>>(mk(d, d, d, 1.0, Y, 1, d, Y, d, 1, 0.0, nullptr, d, 1, 2, H));
     OBC_LAUNCH_CHECK(ctx, "gemm64_kernel");
 
     return obc_check(ctx);
