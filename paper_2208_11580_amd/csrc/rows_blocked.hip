@@ -90,7 +90,7 @@ __global__ __launch_bounds__(256) void blocked_init_kernel(InitArgs a)
         a.ws.diag[(size_t)row * d + j] = (double)a.Hinv[(size_t)j * d + j];
         a.ws.orig[(size_t)row * d + j] = alive ? j : ~j;
         a.ws.blk[(size_t)row * d + j] = 0;
-        a.W_out[(size_t)row * d + j] = 0.f;
+        a.W_out[(size_t)row * d + j] = alive ? a.W[(size_t)row * d + j] : 0.f;   // rows that do no step keep W
         if (a.mode == MODE_QUANT) a.codes[(size_t)row * d + j] = -1;
         dead_local += alive ? 0 : 1;
     }

@@ -280,6 +280,20 @@ def test_end_to_end_tiny_layer(obc, orc):
     assert np.linalg.norm(_np(What) - Wo) <= 1e-4 * np.linalg.norm(Wo)
 
 
+@pytest.mark.parametrize("strategy", [1, 2])
+def test_rows_that_do_no_step_keep_their_weights(obc, strategy):
+    W, X = _layer("conv64x576", d_col=280, d_row=5, n_samples=1500)
+    Hinv = _hinv(obc, X)
+    full = obc.obc_prune_rows(W, Hinv, strategy=strategy, want_trace=True)
+    counts = torch.tensor([0, 1, 70, 0, 280], dtype=torch.int32, device="cuda")
+    rep = obc.obc_prune_rows(W, Hinv, stop_counts=counts, strategy=strategy)
+    obc.obc_check()
+    assert torch.equal(rep["W"], obc.obc_gather_trace(W, full["trace"], counts))
+    assert torch.equal(rep["W"][0], W[0]) and torch.equal(rep["W"][3], W[3])
+    none = obc.obc_prune_rows(W, Hinv, k_steps=0, strategy=strategy)
+    assert torch.equal(none["W"], W)
+
+
 # ------------------------------------------------------------------------------ boundary errors
 def test_argument_errors(obc):
     import paper_2208_11580_amd as pkg
