@@ -5,6 +5,9 @@
 // (d <= 192: the whole loop then never touches HBM) and otherwise in the caller's workspace,
 // where every step streams the live rows of A through the CU with float4 accesses.
 //
+// As in the blocked solver, the O(d) quantities that decide the argmin -- the weights and the
+// maintained diagonal of A -- are kept in fp64; A itself is fp32.
+//
 // Per step: (1) argmin of the score over the live, eligible indices (per-thread scan, wave
 // shuffle reduction, cross-wave LDS reduction; ties to the lowest index); (2) row p of A -- equal
 // to column p, A stays symmetric -- is staged in LDS; (3) w and the maintained diagonal are
@@ -45,29 +48,29 @@ __global__ __launch_bounds__(1024) void rows_rank1_kernel(Rank1Args a)
     const int lane = tid & 63, wave = tid >> 6, nwaves = nthr >> 6;
     const int dpad = (d + 3) & ~3;
 
-    float *w = reinterpret_cast<float *>(smem);
-    float *diag = w + dpad;
-    float *colp = diag + dpad;
+    double *w = reinterpret_cast<double *>(smem);
+    double *diag = w + dpad;
+    float *colp = reinterpret_cast<float *>(diag + dpad);
     float *fcol = colp + dpad;
-    int *lidx = reinterpret_cast<int *>(fcol + dpad);   // compact list of live indices
-    int *pos = lidx + dpad;                             // position of index j in lidx
-    int *dead = pos + dpad;                             // indices removed up front (quant on survivors)
+    uint16_t *lidx = reinterpret_cast<uint16_t *>(fcol + dpad);   // compact list of live indices
+    uint16_t *pos = lidx + dpad;                        // position of index j in lidx (0xffff: not live)
+    uint16_t *dead = pos + dpad;                        // indices removed up front (quant on survivors)
     float *red_s = reinterpret_cast<float *>(dead + dpad);
     int *red_j = reinterpret_cast<int *>(red_s + 32);
     int *misc = red_j + 32;                             // [0] live count, [1] dead count
     uint8_t *blk = reinterpret_cast<uint8_t *>(misc + 8);  // pruned weights per N:M block
     float *A = a.Aws ? a.Aws + (size_t)row * d * d
                      : reinterpret_cast<float *>(smem + obc_align_up(
-                           (size_t)dpad * 7 * 4 + 72 * 4 + (a.nm_m > 0 ? (size_t)dpad : 0), 16));
+                           (size_t)dpad * 30 + 72 * 4 + (a.nm_m > 0 ? (size_t)dpad : 0), 16));
 
     // ---- set-up: private copy of H^-1, the row, the diagonal, the live list
     const float *Hinv = a.Hinv;
     for (size_t e = tid; e < (size_t)d * d; e += nthr) A[e] = Hinv[e];
     for (int j = tid; j < d; j += nthr) {
         bool alive = (MODE == MODE_QUANT && a.live_in) ? (a.live_in[(size_t)row * d + j] != 0) : true;
-        w[j] = alive ? a.W[(size_t)row * d + j] : 0.f;
-        diag[j] = Hinv[(size_t)j * d + j];
-        pos[j] = alive ? 0 : -1;
+        w[j] = alive ? (double)a.W[(size_t)row * d + j] : 0.0;
+        diag[j] = (double)Hinv[(size_t)j * d + j];
+        pos[j] = alive ? 0 : 0xffff;
         if (MODE == MODE_QUANT) a.codes[(size_t)row * d + j] = -1;
     }
     if (a.nm_m > 0)
@@ -76,8 +79,8 @@ __global__ __launch_bounds__(1024) void rows_rank1_kernel(Rank1Args a)
     if (tid == 0) {
         int m = 0, nd = 0;
         for (int j = 0; j < d; ++j) {
-            if (pos[j] == 0) { lidx[m] = j; pos[j] = m; ++m; }
-            else dead[nd++] = j;
+            if (pos[j] == 0) { lidx[m] = (uint16_t)j; pos[j] = (uint16_t)m; ++m; }
+            else dead[nd++] = (uint16_t)j;
         }
         misc[0] = m;
         misc[1] = nd;
@@ -93,9 +96,10 @@ __global__ __launch_bounds__(1024) void rows_rank1_kernel(Rank1Args a)
         sc = sc < 0 ? 0 : sc;
         steps = sc < steps ? sc : steps;
     }
-    float qd = 1.f, qo = 0.f;
-    const float qmax = (float)a.maxq;
-    if (MODE == MODE_QUANT) { qd = a.delta[row]; qo = a.offset[row]; }
+    double qd = 1.0, qo = 0.0;
+    const double qmax = (double)a.maxq;
+    if (MODE == MODE_QUANT) { qd = (double)a.delta[row]; qo = (double)a.offset[row]; }
+    const double iqd = 1.0 / qd;
 
     const bool vec4 = (d % 4 == 0);
     bool failed = false;
@@ -104,21 +108,27 @@ __global__ __launch_bounds__(1024) void rows_rank1_kernel(Rank1Args a)
     // kept on a separate list, so the live list only ever holds survivors
     for (int t = -n_dead; t < steps; ++t) {
         int p;
-        float target = 0.f, wp = 0.f, app;
+        double target = 0.0, wp = 0.0, app;
         if (t < 0) {
             p = dead[t + n_dead];
             app = diag[p];
         } else {
-            // ---- (1) selection
+            // ---- (1) selection: error in fp64, the compared ratio in fp32 (hardware reciprocal)
             Cand c;
             c.s = __builtin_inff();
             c.j = 0x7fffffff;
             for (int q = tid; q < m; q += nthr) {
                 int j = lidx[q];
                 if (a.nm_m > 0 && blk[j / a.nm_m] >= a.nm_m - a.nm_n) continue;
-                float wj = w[j];
-                float tj = (MODE == MODE_QUANT) ? dequant(quant_code(wj, qd, qo, qmax), qd, qo) : 0.f;
-                float s = score_of(wj, tj, diag[j]);
+                double wj = w[j];
+                double tj = 0.0;
+                if (MODE == MODE_QUANT) {
+                    double cq = rint((wj - qo) * iqd);
+                    cq = fmin(fmax(cq, 0.0), qmax);
+                    tj = qo + qd * cq;
+                }
+                double er = tj - wj;
+                float s = (float)(er * er) * __builtin_amdgcn_rcpf((float)diag[j]);
                 if (cand_less(s, j, c.s, c.j)) { c.s = s; c.j = j; }
             }
             c = block_argmin(c, red_s, red_j);
@@ -126,26 +136,28 @@ __global__ __launch_bounds__(1024) void rows_rank1_kernel(Rank1Args a)
             if (p == 0x7fffffff) { failed = true; break; }
             app = diag[p];
             wp = w[p];
-            float code = 0.f;
+            double code = 0.0;
             if (MODE == MODE_QUANT) {
-                code = quant_code(wp, qd, qo, qmax);
-                target = dequant(code, qd, qo);
+                code = rint((wp - qo) / qd);
+                code = fmin(fmax(code, 0.0), qmax);
+                target = qo + qd * code;
             }
             if (tid == 0) {
-                float e = __fsub_rn(target, wp);
+                double e = target - wp;
                 a.order[(size_t)row * a.out_ld + t] = p;
-                a.loss[(size_t)row * a.out_ld + t] = __fdiv_rn(__fmul_rn(e, e), __fmul_rn(2.f, app));
+                a.loss[(size_t)row * a.out_ld + t] = (float)(e * e / (2.0 * app));
                 if (MODE == MODE_QUANT) a.codes[(size_t)row * d + p] = (int)code;
             }
         }
-        if (!(app > 0.f) || !(app < __builtin_inff())) { failed = true; break; }
+        if (!(app > 0.0) || !(app < __builtin_inf())) { failed = true; break; }
+        const float appf = (float)app;
 
         // ---- (2) row p of A (= column p), and the multipliers A[i,p] / A_pp
         const float *Ap = A + (size_t)p * d;
         for (int j = tid; j < d; j += nthr) {
             float v = Ap[j];
             colp[j] = v;
-            fcol[j] = __fdiv_rn(v, app);
+            fcol[j] = __fdiv_rn(v, appf);
         }
         __syncthreads();
 
@@ -156,12 +168,14 @@ __global__ __launch_bounds__(1024) void rows_rank1_kernel(Rank1Args a)
         const int mtot = m + rem;
 
         // ---- (3) compensation of the live weights, maintained diagonal
-        const float g = __fdiv_rn(__fsub_rn(wp, target), app);
+        const double g = (wp - target) / app;
+        const double invapp = 1.0 / app;
         for (int q = tid; q < mtot; q += nthr) {
             int j = (q < m) ? lidx[q] : dead[dnext + q - m];
             if (j == p) continue;
-            if (q < m) w[j] = fmaf(-colp[j], g, w[j]);
-            diag[j] = fmaf(-fcol[j], colp[j], diag[j]);
+            const double cd = (double)colp[j];
+            if (q < m) w[j] -= cd * g;
+            diag[j] -= cd * cd * invapp;
         }
 
         // ---- (4) Lemma 1 on the remaining rows; one wave per row, float4 along the row
@@ -192,9 +206,9 @@ __global__ __launch_bounds__(1024) void rows_rank1_kernel(Rank1Args a)
                 w[p] = target;
                 int qp = pos[p];
                 int last = lidx[m - 1];
-                lidx[qp] = last;
-                pos[last] = qp;
-                pos[p] = -1;
+                lidx[qp] = (uint16_t)last;
+                pos[last] = (uint16_t)qp;
+                pos[p] = 0xffff;
                 if (a.nm_m > 0) blk[p / a.nm_m] += 1;
             }
             m -= 1;
@@ -202,19 +216,19 @@ __global__ __launch_bounds__(1024) void rows_rank1_kernel(Rank1Args a)
         __syncthreads();
         if (t >= 0 && a.trace) {
             float *tr = a.trace + ((size_t)row * a.out_ld + t) * d;
-            for (int j = tid; j < d; j += nthr) tr[j] = w[j];
+            for (int j = tid; j < d; j += nthr) tr[j] = (float)w[j];
         }
     }
 
     if (failed && tid == 0) obc_latch(a.status, OBC_ERR_NUMERIC);
     __syncthreads();
-    for (int j = tid; j < d; j += nthr) a.W_out[(size_t)row * d + j] = w[j];
+    for (int j = tid; j < d; j += nthr) a.W_out[(size_t)row * d + j] = (float)w[j];
 }
 
 inline size_t rank1_vec_lds(int d, int nm_m)
 {
     size_t dpad = (size_t)((d + 3) & ~3);
-    return obc_align_up(dpad * 7 * 4 + 72 * 4 + (nm_m > 0 ? dpad : 0), 16);
+    return obc_align_up(dpad * 30 + 72 * 4 + (nm_m > 0 ? dpad : 0), 16);
 }
 
 constexpr size_t LDS_LIMIT = 160 * 1024;

@@ -159,3 +159,26 @@ def test_compound_prune_then_quantize(obc, orc):
                   live=_np(live[i]))
     print(st)
     assert torch.all(q["W"][mask.bool()] == 0) and torch.all(q["codes"][mask.bool()] == -1)
+
+
+def test_rank1_strategy_at_full_width(obc, orc):
+    """The literal rank-1 schedule at d_col = 2304 (a few rows): same protocol, same tolerances."""
+    import paper_2208_11580_amd as pkg
+
+    W, X, _ = obc_inputs.make_layer("conv256x2304", device="cuda", d_row=4)
+    d = W.shape[1]
+    Hinv = obc.obc_invert(obc.obc_hessian(X))
+    delta, offset, maxq = obc.obc_minmax_grid(W, 4)
+    q = obc.obc_quant_rows(W, Hinv, delta, offset, maxq, strategy=pkg.STRATEGY_RANK1)
+    p = obc.obc_prune_rows(W, Hinv, strategy=pkg.STRATEGY_RANK1)
+    obc.obc_check()
+    st = RowParity()
+    A = _np(Hinv)
+    check_row(orc, st, "quant", A, _np(W[1]), _np(q["order"][1]), _np(q["loss"][1]), _np(q["W"][1]), d,
+              grid=(float(delta[1]), float(offset[1]), maxq), g_codes=_np(q["codes"][1]))
+    check_row(orc, st, "prune", A, _np(W[2]), _np(p["order"][2]), _np(p["loss"][2]), _np(p["W"][2]), d)
+    print(st)
+    # the two strategies take the same decisions
+    qb = obc.obc_quant_rows(W, Hinv, delta, offset, maxq, strategy=pkg.STRATEGY_BLOCKED)
+    assert (q["order"] != qb["order"]).float().mean().item() < 0.002
+    assert (q["codes"] != qb["codes"]).float().mean().item() < 0.002
