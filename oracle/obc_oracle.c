@@ -25,6 +25,11 @@
  *     M - N pruned weights so far.
  *   - quantizer: code = clamp(rne((w - offset) / delta), 0, maxq),
  *     q(w) = offset + delta * code, round-half-to-even.
+ *   - outlier heuristic of Sec. 5 ("Quantization Outliers"), optional: before each argmin, if any
+ *     live weight has a quantization error |q(w_p) - w_p| > delta / 2 (possible only outside the
+ *     clamped range of the grid), the argmin runs over those weights only; same score, same tie
+ *     rule.  The paper gives the threshold as an example and does not say when it is tested;
+ *     this reading is ours.
  *
  * Parity pins live in tests/test_oracle_pins.py (closed-form least squares,
  * loss identity, brute force, Lemma 1 against direct inversion, diagonal-H
@@ -112,6 +117,7 @@ int orc_quant_code(double w, double delta, double offset, int maxq)
  *   w_in     the row's d weights, not modified
  *   k_steps  number of greedy steps (<= d; N:M: <= d (M-N)/M)
  *   nm_n/m   N:M pattern for pruning; nm_m == 0 means unstructured
+ *   outlier  mode 1 only: non-zero switches on the outlier heuristic of Sec. 5
  *   delta, offset, maxq  the row's quantization grid (mode 1)
  *   forced   nullable: take p = forced[t] at step t instead of the argmin
  *            (used to replay another implementation's order); scores are still
@@ -130,7 +136,7 @@ int orc_quant_code(double w, double delta, double offset, int maxq)
  *   live     scratch d bytes; on return 1 for indices never chosen
  * ------------------------------------------------------------------------- */
 int orc_row_solve(int mode, const double *Hinv, int d, const double *w_in, int k_steps,
-                  int nm_n, int nm_m, double delta, double offset, int maxq,
+                  int nm_n, int nm_m, int outlier, double delta, double offset, int maxq,
                   const int32_t *forced, int32_t *order, double *loss, int32_t *codes,
                   double *w_out, double *trace, double *min_score, double *pick_score,
                   double *pre_round, double *A, uint8_t *live)
@@ -153,6 +159,15 @@ int orc_row_solve(int mode, const double *Hinv, int d, const double *w_in, int k
 
     int rc = ORC_OK;
     for (int t = 0; t < k_steps; ++t) {
+        /* outlier heuristic: are there live weights whose quantization error exceeds delta / 2 ? */
+        int any_outlier = 0;
+        if (mode == 1 && outlier) {
+            for (int j = 0; j < d && !any_outlier; ++j) {
+                if (!live[j]) continue;
+                double e = offset + delta * orc_code(w[j], delta, offset, maxq) - w[j];
+                if (fabs(e) > 0.5 * delta) any_outlier = 1;
+            }
+        }
         /* selection: argmin over the live, eligible set */
         int best = -1;
         double best_s = 0.0;
@@ -161,6 +176,7 @@ int orc_row_solve(int mode, const double *Hinv, int d, const double *w_in, int k
             if (use_nm && blk_pruned[j / nm_m] >= nm_m - nm_n) continue;
             double target = (mode == 0) ? 0.0 : offset + delta * orc_code(w[j], delta, offset, maxq);
             double e = target - w[j];
+            if (any_outlier && !(fabs(e) > 0.5 * delta)) continue;
             double s = e * e / A[(size_t)j * d + j];
             if (best < 0 || s < best_s) { best = j; best_s = s; }
         }
@@ -218,7 +234,7 @@ int orc_row_solve(int mode, const double *Hinv, int d, const double *w_in, int k
  * *threads_used.
  * ------------------------------------------------------------------------- */
 int orc_rows_solve(int mode, const double *Hinv, int R, int d, const double *W, int k_steps,
-                   int nm_n, int nm_m, const double *delta, const double *offset, int maxq,
+                   int nm_n, int nm_m, int outlier, const double *delta, const double *offset, int maxq,
                    int32_t *order, double *loss, int32_t *codes, double *W_out, double *trace,
                    int n_threads, int *threads_used)
 {
@@ -240,7 +256,7 @@ int orc_rows_solve(int mode, const double *Hinv, int R, int d, const double *W, 
 #pragma omp for schedule(dynamic, 1)
         for (int i = 0; i < R; ++i) {
             int rc = (A && live) ? orc_row_solve(
-                mode, Hinv, d, W + (size_t)i * d, k_steps, nm_n, nm_m,
+                mode, Hinv, d, W + (size_t)i * d, k_steps, nm_n, nm_m, outlier,
                 mode == 1 ? delta[i] : 1.0, mode == 1 ? offset[i] : 0.0, maxq, NULL,
                 order + (size_t)i * k_steps, loss + (size_t)i * k_steps,
                 codes ? codes + (size_t)i * d : NULL, W_out + (size_t)i * d,

@@ -57,12 +57,12 @@ def _load():
         lib.orc_quant_code.argtypes = [c_double, c_double, c_double, c_int]
         lib.orc_quant_code.restype = c_int
         lib.orc_row_solve.argtypes = [
-            c_int, dp, c_int, dp, c_int, c_int, c_int, c_double, c_double, c_int,
+            c_int, dp, c_int, dp, c_int, c_int, c_int, c_int, c_double, c_double, c_int,
             ip, ip, dp, ip, dp, dp, dp, dp, dp, dp, bp,
         ]
         lib.orc_row_solve.restype = c_int
         lib.orc_rows_solve.argtypes = [
-            c_int, dp, c_int, c_int, dp, c_int, c_int, c_int, dp, dp, c_int,
+            c_int, dp, c_int, c_int, dp, c_int, c_int, c_int, c_int, dp, dp, c_int,
             ip, dp, ip, dp, dp, c_int, POINTER(c_int),
         ]
         lib.orc_rows_solve.restype = c_int
@@ -124,7 +124,7 @@ class RowResult:
 
 
 def _row_solve(mode, Hinv, w, k_steps, nm=(0, 0), grid=(1.0, 0.0, 0), forced=None,
-               want_trace=False):
+               want_trace=False, outlier=False):
     Hinv = np.ascontiguousarray(Hinv, dtype=np.float64)
     w = np.ascontiguousarray(w, dtype=np.float64)
     d = w.shape[0]
@@ -144,7 +144,7 @@ def _row_solve(mode, Hinv, w, k_steps, nm=(0, 0), grid=(1.0, 0.0, 0), forced=Non
     if f is not None:
         assert f.shape[0] >= k_steps
     rc = _load().orc_row_solve(
-        mode, _d(Hinv), d, _d(w), k_steps, int(nm[0]), int(nm[1]),
+        mode, _d(Hinv), d, _d(w), k_steps, int(nm[0]), int(nm[1]), int(bool(outlier)),
         float(grid[0]), float(grid[1]), int(grid[2]), _i(f), _i(r.order), _d(r.loss),
         _i(r.codes), _d(r.w), _d(r.trace), _d(r.min_score), _d(r.pick_score),
         _d(r.pre_round), _d(r.A), _b(r.live),
@@ -178,16 +178,32 @@ def quant_code(w, delta, offset, maxq):
     return _load().orc_quant_code(float(w), float(delta), float(offset), int(maxq))
 
 
-def quant_row(Hinv, w, grid, k_steps=None, forced=None, want_trace=False):
-    """Appendix Algorithm 3 on one row; ``grid = (delta, offset, maxq)``."""
+def symmetric_grid(w_live, bits: int):
+    """Grid symmetric about zero spanning [-max|w|, +max|w|]: (delta, offset, maxq).
+
+    The paper uses symmetric per-channel grids in some experiments (Sec. 6) without giving the
+    formula; this is the plain reading (range symmetric, 2^bits levels).
+    """
+    maxq = (1 << bits) - 1
+    m = float(np.max(np.abs(w_live)))
+    delta = 2.0 * m / maxq if (m > 0 and maxq > 0) else 1.0
+    return delta, -m, maxq
+
+
+def quant_row(Hinv, w, grid, k_steps=None, forced=None, want_trace=False, outlier=False):
+    """Appendix Algorithm 3 on one row; ``grid = (delta, offset, maxq)``.
+
+    ``outlier=True`` switches on the outlier heuristic of Sec. 5 (see obc_oracle.c for the reading).
+    """
     d = len(w)
     if k_steps is None:
         k_steps = d
-    return _row_solve(1, Hinv, w, k_steps, grid=grid, forced=forced, want_trace=want_trace)
+    return _row_solve(1, Hinv, w, k_steps, grid=grid, forced=forced, want_trace=want_trace,
+                      outlier=outlier)
 
 
 # --------------------------------------------------------------------------- many rows
-def _rows_solve(mode, Hinv, W, k_steps, nm, delta, offset, maxq, want_trace, n_threads):
+def _rows_solve(mode, Hinv, W, k_steps, nm, delta, offset, maxq, want_trace, n_threads, outlier=False):
     Hinv = np.ascontiguousarray(Hinv, dtype=np.float64)
     W = np.ascontiguousarray(W, dtype=np.float64)
     R, d = W.shape
@@ -200,7 +216,7 @@ def _rows_solve(mode, Hinv, W, k_steps, nm, delta, offset, maxq, want_trace, n_t
     of = np.ascontiguousarray(offset, dtype=np.float64) if offset is not None else None
     used = c_int(0)
     rc = _load().orc_rows_solve(
-        mode, _d(Hinv), R, d, _d(W), k_steps, int(nm[0]), int(nm[1]), _d(dl), _d(of),
+        mode, _d(Hinv), R, d, _d(W), k_steps, int(nm[0]), int(nm[1]), int(bool(outlier)), _d(dl), _d(of),
         int(maxq), _i(order), _d(loss), _i(codes), _d(W_out), _d(trace), int(n_threads),
         ctypes.byref(used),
     )
@@ -216,8 +232,8 @@ def prune_rows(Hinv, W, k_steps=None, nm=(0, 0), want_trace=False, n_threads=0):
     return _rows_solve(0, Hinv, W, k_steps, nm, None, None, 0, want_trace, n_threads)
 
 
-def quant_rows(Hinv, W, delta, offset, maxq, n_threads=0):
-    return _rows_solve(1, Hinv, W, W.shape[1], (0, 0), delta, offset, maxq, False, n_threads)
+def quant_rows(Hinv, W, delta, offset, maxq, n_threads=0, outlier=False):
+    return _rows_solve(1, Hinv, W, W.shape[1], (0, 0), delta, offset, maxq, False, n_threads, outlier)
 
 
 # --------------------------------------------------------------------------- global step

@@ -487,3 +487,83 @@ def test_oracle_reproduces_its_golden_fixture(orc):
     assert q["codes"].tolist() == g["quant_codes"] and q["order"].tolist() == g["quant_order"]
     nm = orc.prune_rows(A, W, nm=(2, 4))
     assert nm["order"].tolist() == g["nm24_order"]
+
+
+# ----------------------------------------------------------------------------- outlier heuristic
+def _narrow_grid(orc, w, bits):
+    g = orc.minmax_grid(w, bits)
+    # a grid covering only the middle of the weight range: several weights start as outliers
+    return (0.55 * g[0], g[1] + 0.22 * g[0] * g[2], g[2])
+
+
+def test_outlier_heuristic_is_inactive_without_outliers(orc):
+    d = 22
+    W, X = _problem(501, d)
+    A = orc.invert(orc.hessian(X))
+    g = orc.minmax_grid(W[0], 4)
+    wide = (3.0 * g[0], g[1] - g[0] * g[2], g[2])        # range three times the weights' range
+    a = orc.quant_row(A, W[0], wide, want_trace=True)
+    b = orc.quant_row(A, W[0], wide, outlier=True, want_trace=True)
+    # no weight ever leaves the grid's range here, so there is never an outlier
+    err = np.abs(a.trace - (wide[1] + wide[0] * np.clip(np.rint((a.trace - wide[1]) / wide[0]), 0, wide[2])))
+    assert err.max() <= wide[0] / 2
+    assert np.array_equal(a.order, b.order) and np.array_equal(a.codes, b.codes)
+    assert np.array_equal(a.loss, b.loss) and np.array_equal(a.w, b.w)
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_outlier_heuristic_matches_restricted_brute_force(orc, seed):
+    """Reading of Sec. 5 'Quantization Outliers': while any live weight has |q(w)-w| > delta/2 the
+    greedy choice runs over those weights only; the pick minimises the loss increase among them."""
+    d = 6 + seed % 3
+    W, X = _problem(520 + seed, d)
+    H = orc.hessian(X)
+    w0 = W[0]
+    delta, offset, maxq = _narrow_grid(orc, w0, 2)
+    r = orc.quant_row(orc.invert(H), w0, (delta, offset, maxq), outlier=True, want_trace=True)
+    q = lambda v: offset + delta * float(np.clip(np.rint((v - offset) / delta), 0, maxq))
+    fixed, vals, cur, base = [], [], w0.copy(), 0.0
+    saw_outlier_step = False
+    for t in range(d):
+        live = [p for p in range(d) if p not in fixed]
+        outl = [p for p in live if abs(q(cur[p]) - cur[p]) > delta / 2]
+        cands = outl if outl else live
+        saw_outlier_step |= bool(outl)
+        best, best_cost, best_q = None, None, None
+        for p in cands:
+            v = _ls_on_support(H, w0, fixed + [p], np.array(vals + [q(cur[p])]))
+            cost = _quad(H, w0, v)
+            if best is None or cost < best_cost:
+                best, best_cost, best_q = p, cost, q(cur[p])
+        assert r.order[t] == best
+        assert np.isclose(r.loss[t], best_cost - base, rtol=1e-6, atol=1e-13)
+        fixed.append(best)
+        vals.append(best_q)
+        cur = _ls_on_support(H, w0, fixed, np.array(vals))
+        assert np.allclose(r.trace[t], cur, rtol=1e-7, atol=1e-10)
+        base = best_cost
+    assert saw_outlier_step
+    assert np.isclose(r.loss.sum(), _quad(H, w0, r.w), rtol=1e-8)          # loss identity still holds
+    assert np.array_equal(r.w, offset + delta * r.codes)                   # codes on the grid
+
+
+def test_outlier_heuristic_lowers_the_error_on_a_clipping_grid(orc):
+    d = 40
+    W, X = _problem(540, d)
+    H = orc.hessian(X)
+    A = orc.invert(H)
+    grid = _narrow_grid(orc, W[0], 3)
+    plain = orc.quant_row(A, W[0], grid)
+    heur = orc.quant_row(A, W[0], grid, outlier=True)
+    assert not np.array_equal(plain.order, heur.order)
+    assert _quad(H, W[0], heur.w) < _quad(H, W[0], plain.w)
+
+
+def test_symmetric_grid_is_symmetric_about_zero(orc):
+    w = np.array([-0.31, 0.12, 0.05, 0.27, -0.02])
+    for bits in (2, 3, 4, 8):
+        delta, offset, maxq = orc.symmetric_grid(w, bits)
+        levels = offset + delta * np.arange(maxq + 1)
+        assert np.isclose(levels[0], -0.31) and np.isclose(levels[-1], 0.31)
+        assert np.allclose(levels, -levels[::-1])
+    assert orc.symmetric_grid(np.zeros(3), 4) == (1.0, -0.0, 15) or orc.symmetric_grid(np.zeros(3), 4)[0] == 1.0
