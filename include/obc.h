@@ -123,8 +123,14 @@ int obc_prune_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d
                    int nm_n, int nm_m, const int32_t *stop_counts, int32_t *order, float *loss,
                    float *W_out, float *trace, int strategy, void *ws, size_t ws_bytes);
 
+/* Flags of obc_quant_rows. */
+#define OBC_QUANT_OUTLIERS 1   /* Sec. 5 "Quantization Outliers": while any live weight of the row has
+                                  a quantization error |q(w) - w| > delta / 2, the greedy choice runs
+                                  over those weights only (same score, same tie rule) */
+
 /* Quantize every row with Algorithm 3 on the caller's per-row uniform grid
  *   q(w) = offset[i] + delta[i] * clamp(rne((w - offset[i]) / delta[i]), 0, maxq).
+ *   flags    0 or OBC_QUANT_OUTLIERS
  *   live     nullable, R x d: 0 marks an already pruned weight; those are first removed from the
  *            row's inverse (Lemma 1, no weight change) so that OBQ runs on the dense sub-problem
  *            of the survivors; they keep weight 0 and get code -1.
@@ -132,14 +138,16 @@ int obc_prune_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d
  *   codes    R x d int32 out: grid code of each weight at the moment it was chosen
  *   W_out    R x d out: dequantized weights offset + delta * code */
 int obc_quant_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d,
-                   const float *delta, const float *offset, int maxq, const uint8_t *live,
+                   const float *delta, const float *offset, int maxq, const uint8_t *live, int flags,
                    int32_t *order, float *loss, int32_t *codes, float *W_out, int strategy,
                    void *ws, size_t ws_bytes);
 
-/* Per-row asymmetric min-max grid over the live weights: offset = min, delta = (max - min)/maxq
- * (delta = 1 when max == min or no weight is live).  live nullable = all live. */
+/* Per-row grid over the live weights (live nullable = all live).
+ *   symmetric == 0: asymmetric min-max grid, offset = min, delta = (max - min) / maxq
+ *   symmetric != 0: grid symmetric about zero, offset = -max|w|, delta = 2 max|w| / maxq
+ * delta = 1 when the range is empty (constant row, all-zero row, no live weight). */
 int obc_minmax_grid(obc_ctx *ctx, const float *W, const uint8_t *live, int R, int d, int maxq,
-                    float *delta, float *offset);
+                    int symmetric, float *delta, float *offset);
 
 /* ---- Appendix Algorithm 2: the global step ---------------------------------------------
  * From the per-row loss traces (loss, order: R x d as written by obc_prune_rows with

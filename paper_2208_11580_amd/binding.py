@@ -20,6 +20,7 @@ OBC_OK = 0
 OBC_ERR_BAD_ARG, OBC_ERR_BAD_SHAPE, OBC_ERR_NOT_SPD = -1, -2, -3
 OBC_ERR_WORKSPACE, OBC_ERR_NUMERIC, OBC_ERR_HIP = -4, -5, -6
 STRATEGY_AUTO, STRATEGY_RANK1, STRATEGY_BLOCKED = 0, 1, 2
+QUANT_OUTLIERS = 1
 
 EXPORTS = [
     "obc_create", "obc_destroy", "obc_last_error", "obc_version", "obc_check",
@@ -75,9 +76,9 @@ def load_library():
     lib.obc_rows_workspace_bytes.argtypes = [c_int, c_int, c_int, sp]
     lib.obc_prune_rows.argtypes = [vp, vp, vp, c_int, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp,
                                    c_int, vp, c_size_t]
-    lib.obc_quant_rows.argtypes = [vp, vp, vp, c_int, c_int, vp, vp, c_int, vp, vp, vp, vp, vp, c_int,
+    lib.obc_quant_rows.argtypes = [vp, vp, vp, c_int, c_int, vp, vp, c_int, vp, c_int, vp, vp, vp, vp, c_int,
                                    vp, c_size_t]
-    lib.obc_minmax_grid.argtypes = [vp, vp, vp, c_int, c_int, c_int, vp, vp]
+    lib.obc_minmax_grid.argtypes = [vp, vp, vp, c_int, c_int, c_int, c_int, vp, vp]
     lib.obc_global_select_workspace_bytes.argtypes = [c_int, c_int, sp]
     lib.obc_global_select.argtypes = [vp, vp, vp, c_int, c_int, c_int64, vp, vp, vp, c_size_t]
     lib.obc_gather_trace.argtypes = [vp, vp, vp, vp, c_int, c_int, c_int, vp]
@@ -210,16 +211,17 @@ class Context:
             int(strategy), c_void_p(ws.data_ptr()), ws.numel()))
         return dict(order=order, loss=loss, W=W_out, trace=trace)
 
-    def obc_minmax_grid(self, W, bits, live=None):
+    def obc_minmax_grid(self, W, bits, live=None, symmetric=False):
         R, d = W.shape
         maxq = (1 << bits) - 1
         delta = torch.empty(R, dtype=torch.float32, device=W.device)
         offset = torch.empty(R, dtype=torch.float32, device=W.device)
         self._ck(self.lib.obc_minmax_grid(self.h, _ptr(W, torch.float32), _ptr(live, torch.uint8), R, d,
-                                          maxq, _ptr(delta), _ptr(offset)))
+                                          maxq, int(bool(symmetric)), _ptr(delta), _ptr(offset)))
         return delta, offset, maxq
 
-    def obc_quant_rows(self, W, Hinv, delta, offset, maxq, live=None, strategy=STRATEGY_AUTO, out=None):
+    def obc_quant_rows(self, W, Hinv, delta, offset, maxq, live=None, strategy=STRATEGY_AUTO, out=None,
+                       outliers=False):
         R, d = W.shape
         dev = W.device
         if out is None:
@@ -239,7 +241,8 @@ class Context:
         ws = self.workspace(self.rows_workspace_bytes(R, d, strategy))
         self._ck(self.lib.obc_quant_rows(
             self.h, _ptr(W, torch.float32), _ptr(Hinv, torch.float32), R, d, _ptr(delta, torch.float32),
-            _ptr(offset, torch.float32), int(maxq), _ptr(live, torch.uint8), _ptr(order), _ptr(loss),
+            _ptr(offset, torch.float32), int(maxq), _ptr(live, torch.uint8), QUANT_OUTLIERS if outliers else 0,
+            _ptr(order), _ptr(loss),
             _ptr(codes), _ptr(W_out), int(strategy), c_void_p(ws.data_ptr()), ws.numel()))
         return dict(order=order, loss=loss, codes=codes, W=W_out)
 

@@ -128,7 +128,7 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
         if (!st.alive[e]) continue;
         float sc;
         if (st.og[e] < 0) {
-            sc = -1.f;
+            sc = -__builtin_inff();   // dead indices go first, before any outlier
         } else {
             if (a.nm_m > 0 && blk[st.og[e] / a.nm_m] >= a.nm_m - a.nm_n) continue;
             double tq = 0.0;
@@ -139,6 +139,9 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
             }
             double er = tq - st.w[e];
             sc = (float)(er * er) * __builtin_amdgcn_rcpf((float)st.dg[e]);
+            // outlier heuristic: a weight whose error exceeds half a grid step sorts before every
+            // non-outlier
+            if (MODE == MODE_QUANT && a.outliers && fabs(er) > 0.5 * pr.qd) sc = outlier_first(sc);
         }
         if (sc == sc) {   // a NaN score is no candidate
             unsigned long long k = ((unsigned long long)score_bits(sc) << 32) | (unsigned)(tid + e * T);

@@ -7,13 +7,13 @@ bool rank1_lds_resident(int d, int nm_m);
 size_t rank1_workspace_bytes(int R, int d);
 int rank1_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, int R, int d, int k_steps,
                  int nm_n, int nm_m, const int32_t *stop_counts, const float *delta,
-                 const float *offset, int maxq, const uint8_t *live, int32_t *order, float *loss,
+                 const float *offset, int maxq, const uint8_t *live, int flags, int32_t *order, float *loss,
                  int32_t *codes, float *W_out, float *trace, int out_ld, void *ws, size_t ws_bytes);
 size_t blocked_workspace_bytes(int R, int d);
 int blocked_max_d();
 int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, int R, int d, int k_steps,
                    int nm_n, int nm_m, const int32_t *stop_counts, const float *delta,
-                   const float *offset, int maxq, const uint8_t *live, int32_t *order, float *loss,
+                   const float *offset, int maxq, const uint8_t *live, int flags, int32_t *order, float *loss,
                    int32_t *codes, float *W_out, float *trace, int out_ld, void *ws, size_t ws_bytes);
 }  // namespace obc_rows
 
@@ -28,10 +28,11 @@ int pick_strategy(int strategy, int d)
     return d <= blocked_max_d() ? OBC_STRATEGY_BLOCKED : OBC_STRATEGY_RANK1;
 }
 
-// offset = min, delta = (max - min) / maxq over the live weights of each row; one wave per row.
+// The row's grid over its live weights (min-max, or symmetric about zero); one wave per row.
 __global__ __launch_bounds__(256) void minmax_grid_kernel(const float *__restrict__ W,
                                                           const uint8_t *__restrict__ live, int R,
-                                                          int d, int maxq, float *__restrict__ delta,
+                                                          int d, int maxq, int symmetric,
+                                                          float *__restrict__ delta,
                                                           float *__restrict__ offset)
 {
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -50,9 +51,16 @@ __global__ __launch_bounds__(256) void minmax_grid_kernel(const float *__restric
         hi = fmaxf(hi, __shfl_xor(hi, off, 64));
     }
     if (lane == 0) {
-        bool ok = (hi > lo) && maxq > 0;
-        delta[row] = ok ? __fdiv_rn(__fsub_rn(hi, lo), (float)maxq) : 1.f;
-        offset[row] = (lo <= hi) ? lo : 0.f;
+        if (symmetric) {
+            float m = (lo <= hi) ? fmaxf(fabsf(lo), fabsf(hi)) : 0.f;
+            bool ok = (m > 0.f) && maxq > 0;
+            delta[row] = ok ? __fdiv_rn(__fmul_rn(2.f, m), (float)maxq) : 1.f;
+            offset[row] = -m;
+        } else {
+            bool ok = (hi > lo) && maxq > 0;
+            delta[row] = ok ? __fdiv_rn(__fsub_rn(hi, lo), (float)maxq) : 1.f;
+            offset[row] = (lo <= hi) ? lo : 0.f;
+        }
     }
 }
 
@@ -106,13 +114,13 @@ int obc_prune_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d
     int s = pick_strategy(strategy, d);
     if (s == OBC_STRATEGY_RANK1)
         return rank1_launch(ctx, MODE_PRUNE, W, Hinv, R, d, k_steps, nm_n, nm_m, stop_counts, nullptr,
-                            nullptr, 0, nullptr, order, loss, nullptr, W_out, trace, k_steps, ws, ws_bytes);
+                            nullptr, 0, nullptr, 0, order, loss, nullptr, W_out, trace, k_steps, ws, ws_bytes);
     return blocked_launch(ctx, MODE_PRUNE, W, Hinv, R, d, k_steps, nm_n, nm_m, stop_counts, nullptr,
-                          nullptr, 0, nullptr, order, loss, nullptr, W_out, trace, k_steps, ws, ws_bytes);
+                          nullptr, 0, nullptr, 0, order, loss, nullptr, W_out, trace, k_steps, ws, ws_bytes);
 }
 
 int obc_quant_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d,
-                   const float *delta, const float *offset, int maxq, const uint8_t *live,
+                   const float *delta, const float *offset, int maxq, const uint8_t *live, int flags,
                    int32_t *order, float *loss, int32_t *codes, float *W_out, int strategy,
                    void *ws, size_t ws_bytes)
 {
@@ -122,25 +130,27 @@ int obc_quant_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d
         return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_quant_rows: null argument");
     if (maxq < 0 || maxq > (1 << 16))
         return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_quant_rows: maxq (%d) out of range", maxq);
+    if (flags & ~OBC_QUANT_OUTLIERS)
+        return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_quant_rows: unknown flags 0x%x", flags);
     if (strategy < OBC_STRATEGY_AUTO || strategy > OBC_STRATEGY_BLOCKED)
         return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_quant_rows: unknown strategy %d", strategy);
     if (R == 0) return OBC_OK;
     int s = pick_strategy(strategy, d);
     if (s == OBC_STRATEGY_RANK1)
         return rank1_launch(ctx, MODE_QUANT, W, Hinv, R, d, d, 0, 0, nullptr, delta, offset, maxq, live,
-                            order, loss, codes, W_out, nullptr, d, ws, ws_bytes);
+                            flags, order, loss, codes, W_out, nullptr, d, ws, ws_bytes);
     return blocked_launch(ctx, MODE_QUANT, W, Hinv, R, d, d, 0, 0, nullptr, delta, offset, maxq, live,
-                          order, loss, codes, W_out, nullptr, d, ws, ws_bytes);
+                          flags, order, loss, codes, W_out, nullptr, d, ws, ws_bytes);
 }
 
 int obc_minmax_grid(obc_ctx *ctx, const float *W, const uint8_t *live, int R, int d, int maxq,
-                    float *delta, float *offset)
+                    int symmetric, float *delta, float *offset)
 {
     if (!ctx) return OBC_ERR_BAD_ARG;
     if (!W || !delta || !offset) return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_minmax_grid: null argument");
     if (R < 0 || d <= 0 || maxq < 0) return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_minmax_grid: bad size");
     if (R == 0) return OBC_OK;
-    minmax_grid_kernel<<<(R + 3) / 4, 256, 0, ctx->stream>>>(W, live, R, d, maxq, delta, offset);
+    minmax_grid_kernel<<<(R + 3) / 4, 256, 0, ctx->stream>>>(W, live, R, d, maxq, symmetric, delta, offset);
     OBC_LAUNCH_CHECK(ctx, "minmax_grid_kernel");
     return OBC_OK;
 }

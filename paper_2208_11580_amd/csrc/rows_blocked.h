@@ -52,6 +52,7 @@ struct PanelArgs {
     int nm_n, nm_m;
     const float *delta, *offset;
     int maxq;
+    int outliers;            // OBQ: restrict the choice to outliers while there are any
     BlockedWs ws;
     int32_t *order;
     float *loss;

@@ -330,7 +330,7 @@ size_t blocked_workspace_bytes(int R, int d) { return carve(nullptr, nullptr, R,
 
 int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, int R, int d, int k_steps,
                    int nm_n, int nm_m, const int32_t *stop_counts, const float *delta,
-                   const float *offset, int maxq, const uint8_t *live, int32_t *order, float *loss,
+                   const float *offset, int maxq, const uint8_t *live, int flags, int32_t *order, float *loss,
                    int32_t *codes, float *W_out, float *trace, int out_ld, void *ws, size_t ws_bytes)
 {
     if (d > blocked_max_d())
@@ -357,7 +357,7 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
     PanelArgs pa;
     pa.d = d; pa.nm_n = nm_n; pa.nm_m = nm_m; pa.delta = delta; pa.offset = offset; pa.maxq = maxq;
     pa.ws = bw; pa.order = order; pa.loss = loss; pa.codes = codes; pa.W_out = W_out; pa.trace = trace;
-    pa.out_ld = out_ld; pa.status = ctx->d_status;
+    pa.out_ld = out_ld; pa.status = ctx->d_status; pa.outliers = (flags & OBC_QUANT_OUTLIERS) ? 1 : 0;
     FlushArgs fa;
     fa.d = d; fa.R = R; fa.ws = bw;
 

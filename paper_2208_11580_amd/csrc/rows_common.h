@@ -42,6 +42,17 @@ __device__ inline float score_of(float w, float target, float app)
     return __fdiv_rn(__fmul_rn(e, e), app);
 }
 
+// Outlier heuristic of Sec. 5: the score s >= 0 of an outlier is mapped, order-preserving and
+// without loss (a reflection of its bit pattern), into the finite negative floats, so that every
+// outlier sorts before every non-outlier and outliers keep their order among themselves.
+__device__ inline float outlier_first(float s)
+{
+    unsigned u = __float_as_uint(s);
+    if ((u & 0x80000000u) || s != s) return s;  // a negative or NaN score (broken diagonal) stays
+    u = u < 0x7EFFFFFFu ? u : 0x7EFFFFFFu;      // keeps the image a normal number (scores above 1.7e38 tie)
+    return __uint_as_float(0x80000000u | (0x7F7FFFFFu - u));
+}
+
 __device__ inline Cand wave_argmin(Cand c)
 {
 #pragma unroll

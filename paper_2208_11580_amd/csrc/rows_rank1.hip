@@ -29,6 +29,7 @@ struct Rank1Args {
     const float *delta, *offset;
     int maxq;
     const uint8_t *live_in;
+    int outliers;            // OBQ: restrict the choice to outliers while there are any
     int32_t *order;
     float *loss;
     int32_t *codes;
@@ -129,6 +130,8 @@ __global__ __launch_bounds__(1024) void rows_rank1_kernel(Rank1Args a)
                 }
                 double er = tj - wj;
                 float s = (float)(er * er) * __builtin_amdgcn_rcpf((float)diag[j]);
+                // an outlier (error beyond half a grid step) sorts before every non-outlier
+                if (MODE == MODE_QUANT && a.outliers && fabs(er) > 0.5 * qd) s = outlier_first(s);
                 if (cand_less(s, j, c.s, c.j)) { c.s = s; c.j = j; }
             }
             c = block_argmin(c, red_s, red_j);
@@ -251,10 +254,11 @@ size_t rank1_workspace_bytes(int R, int d)
 
 int rank1_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, int R, int d, int k_steps,
                  int nm_n, int nm_m, const int32_t *stop_counts, const float *delta,
-                 const float *offset, int maxq, const uint8_t *live, int32_t *order, float *loss,
+                 const float *offset, int maxq, const uint8_t *live, int flags, int32_t *order, float *loss,
                  int32_t *codes, float *W_out, float *trace, int out_ld, void *ws, size_t ws_bytes)
 {
     Rank1Args a;
+    a.outliers = (flags & OBC_QUANT_OUTLIERS) ? 1 : 0;
     a.W = W; a.Hinv = Hinv; a.R = R; a.d = d; a.k_steps = k_steps; a.nm_n = nm_n; a.nm_m = nm_m;
     a.stop_counts = stop_counts; a.delta = delta; a.offset = offset; a.maxq = maxq; a.live_in = live;
     a.order = order; a.loss = loss; a.codes = codes; a.W_out = W_out; a.trace = trace;

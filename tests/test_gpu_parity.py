@@ -166,9 +166,12 @@ def test_strategies_agree_on_order(obc):
 
 
 # ------------------------------------------------------------------------------ OBQ rows
-def _check_quant(obc, orc, W, Hinv, bits, strategy, live=None, rows=None):
-    delta, offset, maxq = obc.obc_minmax_grid(W, bits, live=live)
-    res = obc.obc_quant_rows(W, Hinv, delta, offset, maxq, live=live, strategy=strategy)
+def _check_quant(obc, orc, W, Hinv, bits, strategy, live=None, rows=None, grid=None, outliers=False):
+    if grid is None:
+        delta, offset, maxq = obc.obc_minmax_grid(W, bits, live=live)
+    else:
+        delta, offset, maxq = grid
+    res = obc.obc_quant_rows(W, Hinv, delta, offset, maxq, live=live, strategy=strategy, outliers=outliers)
     obc.obc_check()
     A, Wn = _np(Hinv), _np(W)
     dl, of = _np(delta), _np(offset)
@@ -177,13 +180,14 @@ def _check_quant(obc, orc, W, Hinv, bits, strategy, live=None, rows=None):
     order, loss, Wo, codes = _np(res["order"]), _np(res["loss"]), _np(res["W"]), _np(res["codes"])
     for i in (range(W.shape[0]) if rows is None else rows):
         wl = Wn[i] if lv is None else Wn[i][lv[i] != 0]
-        # the grid the GPU computed is the oracle's min-max grid of the same fp32 weights
-        g = orc.minmax_grid(wl.astype(np.float64), bits)
-        assert np.float32(g[1]) == of[i] and np.isclose(g[0], dl[i], rtol=1e-6)
+        if grid is None:
+            # the grid the GPU computed is the oracle's min-max grid of the same fp32 weights
+            g = orc.minmax_grid(wl.astype(np.float64), bits)
+            assert np.float32(g[1]) == of[i] and np.isclose(g[0], dl[i], rtol=1e-6)
         k = len(wl)
         check_row(orc, st, "quant", A, Wn[i], order[i], loss[i], Wo[i], k,
                   grid=(float(dl[i]), float(of[i]), maxq), g_codes=codes[i],
-                  live=None if lv is None else lv[i])
+                  live=None if lv is None else lv[i], outlier=outliers)
     print(st)
     return res, st
 
@@ -195,6 +199,62 @@ def test_quant_rows_matches_oracle(obc, orc, strategy, d, R, bits):
     W, X = _layer(name, d_col=d, d_row=R, n_samples=max(256, 3 * d))
     Hinv = _hinv(obc, X)
     _check_quant(obc, orc, W, Hinv, bits, strategy)
+
+
+def _narrow_grid(W, bits, shrink):
+    """A min-max grid shrunk about its centre: the weights beyond it start as outliers."""
+    maxq = (1 << bits) - 1
+    lo, hi = W.min(dim=1).values, W.max(dim=1).values
+    mid, half = 0.5 * (lo + hi), 0.5 * (hi - lo) * shrink
+    return (2.0 * half / maxq).contiguous(), (mid - half).contiguous(), maxq
+
+
+@pytest.mark.parametrize("strategy", [1, 2])
+@pytest.mark.parametrize("d,R,bits,shrink", [(32, 16, 3, 0.5), (203, 4, 3, 0.6), (576, 4, 4, 0.7), (768, 3, 2, 0.5)])
+def test_quant_rows_outlier_heuristic_matches_oracle(obc, orc, strategy, d, R, bits, shrink):
+    # Sec. 5, outlier heuristic: on a grid narrower than the weight range several weights start
+    # beyond half a step from the grid, and compensation pushes more of them out on the way
+    name = "lin16x32" if d == 32 else ("attn768x768" if d == 768 else "conv64x576")
+    W, X = _layer(name, d_col=d, d_row=R, n_samples=max(256, 3 * d))
+    Hinv = _hinv(obc, X)
+    grid = _narrow_grid(W, bits, shrink)
+    res, st = _check_quant(obc, orc, W, Hinv, bits, strategy, grid=grid, outliers=True)
+    # the heuristic changed the outcome (else the case does not test it)
+    plain = obc.obc_quant_rows(W, Hinv, *grid, strategy=strategy)
+    assert not torch.equal(plain["order"], res["order"])
+
+
+@pytest.mark.parametrize("strategy", [1, 2])
+def test_outlier_heuristic_is_inactive_on_a_covering_grid(obc, strategy):
+    # on the min-max grid no weight starts as an outlier; the flag only matters once compensation
+    # has pushed a weight out, so with a very wide grid both runs are bit-identical
+    W, X = _layer("conv64x576", d_col=260, d_row=4, n_samples=2000)
+    Hinv = _hinv(obc, X)
+    delta, offset, maxq = obc.obc_minmax_grid(W, 8)
+    wide = (delta * 4, offset - delta * 4 * 384, 1023)
+    a = obc.obc_quant_rows(W, Hinv, *wide, strategy=strategy)
+    b = obc.obc_quant_rows(W, Hinv, *wide, strategy=strategy, outliers=True)
+    for k in ("order", "loss", "codes", "W"):
+        assert torch.equal(a[k], b[k])
+
+
+def test_symmetric_grid_matches_oracle(obc, orc):
+    W, _ = _layer("conv64x576", d_col=203, d_row=8, n_samples=256)
+    W[3] = 0.0                       # empty range
+    live = (torch.rand_like(W) > 0.3).to(torch.uint8)
+    live[5] = 0                      # no live weight
+    for lv in (None, live):
+        delta, offset, maxq = obc.obc_minmax_grid(W, 4, live=lv, symmetric=True)
+        Wn = _np(W)
+        for i in range(W.shape[0]):
+            wl = Wn[i] if lv is None else Wn[i][_np(lv)[i] != 0]
+            if wl.size == 0:
+                assert delta[i].item() == 1.0 and offset[i].item() == 0.0
+                continue
+            g = orc.symmetric_grid(wl.astype(np.float64), 4)
+            assert np.float32(g[1]) == offset[i].item()
+            assert np.isclose(g[0], delta[i].item(), rtol=1e-6)
+            assert maxq == g[2]
 
 
 @pytest.mark.parametrize("strategy", [1, 2])
