@@ -149,6 +149,35 @@ int obc_quant_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d
 int obc_minmax_grid(obc_ctx *ctx, const float *W, const uint8_t *live, int R, int d, int maxq,
                     int symmetric, float *delta, float *offset);
 
+/* ---- Appendix "Sequential Quantization with OBQ": re-fit of the dense weights ------------
+ * When the layer's inputs X come from the already compressed model, the dense weights are first
+ * re-optimised for them by the closed form of linear regression, W^T = (X X^T)^-1 X Y^T (Y = the
+ * dense model's outputs of this layer, d_row x N); then their gradient is zero again and OBQ
+ * applies.  With H = 2 X X^T (+ dampening, as obc_hessian forms it) and C = 2 Y X^T this is
+ * W = C H^-1: the minimiser of the quadratic whose Hessian the row solvers use.  C is accumulated
+ * over batches like H. */
+
+/* Workspace of obc_cross. */
+int obc_cross_workspace_bytes(int d_row, int d_col, int64_t N, size_t *bytes);
+
+/* C (d_row x d_col, device, row-major) = 2 Y X^T, or C += 2 Y X^T when accumulate != 0.
+ *   X  device, d_col x N, leading dimension ldx >= N;  Y  device, d_row x N, ldy >= N.
+ * fp32 matrix cores, fixed summation order (deterministic).  Errors as obc_hessian. */
+int obc_cross(obc_ctx *ctx, const float *X, const float *Y, int d_col, int d_row, int64_t N, int64_t ldx,
+              int64_t ldy, int accumulate, float *C, void *ws, size_t ws_bytes);
+
+/* Workspace of obc_refit. */
+int obc_refit_workspace_bytes(int d_col, int d_row, size_t *bytes);
+
+/* W_out (d_row x d_col, device) = C H^-1 through the fp64 Cholesky factor of H (H^-1 itself is
+ * never rounded to fp32 on the way).
+ *   H   device, d_col x d_col, the dampened Hessian; left untouched when invert_in_place == 0,
+ *       replaced by its inverse exactly as obc_invert does otherwise (the factorisation is shared)
+ *   C   device, d_row x d_col, from obc_cross
+ * Synchronises.  OBC_ERR_NOT_SPD as obc_invert. */
+int obc_refit(obc_ctx *ctx, float *H, int d_col, const float *C, int d_row, float *W_out,
+              int invert_in_place, void *ws, size_t ws_bytes);
+
 /* ---- Appendix Algorithm 2: the global step ---------------------------------------------
  * From the per-row loss traces (loss, order: R x d as written by obc_prune_rows with
  * k_steps == d) find how many weights each row gives up when k weights are pruned from the

@@ -115,6 +115,27 @@ def invert(H):
     return A
 
 
+def cross(X, Y):
+    """C = 2 Y X^T in fp64 (X is d_col x N, Y is d_row x N): the second moment that the sequential
+    variant accumulates beside the Hessian (appendix "Sequential Quantization with OBQ")."""
+    X = np.asarray(X, dtype=np.float64)
+    Y = np.asarray(Y, dtype=np.float64)
+    return 2.0 * (Y @ X.T)
+
+
+def refit(H, C):
+    """Dense weights re-optimised for new inputs (appendix "Sequential Quantization with OBQ").
+
+    The closed form of linear regression, W^T = (X X^T)^-1 X Y^T, written with the quantities the
+    method already holds: H = 2 X X^T and C = 2 Y X^T give W^T = H^-1 C^T.  With a dampened H this is
+    the minimiser of the quadratic whose Hessian the row solver assumes (gradient W H - C = 0).
+    The linear system is solved by the library routine; H^-1 is not formed.
+    """
+    H = np.asarray(H, dtype=np.float64)
+    C = np.asarray(C, dtype=np.float64)
+    return np.linalg.solve(H, C.T).T
+
+
 # --------------------------------------------------------------------------- one row
 class RowResult:
     """Outputs of one greedy row run (arrays are fp64 / int32 numpy)."""

@@ -27,6 +27,7 @@ EXPORTS = [
     "obc_profile_begin", "obc_profile_end",
     "obc_hessian_workspace_bytes", "obc_hessian",
     "obc_invert_workspace_bytes", "obc_invert",
+    "obc_cross_workspace_bytes", "obc_cross", "obc_refit_workspace_bytes", "obc_refit",
     "obc_rows_workspace_bytes", "obc_prune_rows", "obc_quant_rows", "obc_minmax_grid",
     "obc_global_select_workspace_bytes", "obc_global_select", "obc_gather_trace",
 ]
@@ -79,6 +80,10 @@ def load_library():
     lib.obc_quant_rows.argtypes = [vp, vp, vp, c_int, c_int, vp, vp, c_int, vp, c_int, vp, vp, vp, vp, c_int,
                                    vp, c_size_t]
     lib.obc_minmax_grid.argtypes = [vp, vp, vp, c_int, c_int, c_int, c_int, vp, vp]
+    lib.obc_cross_workspace_bytes.argtypes = [c_int, c_int, c_int64, sp]
+    lib.obc_cross.argtypes = [vp, vp, vp, c_int, c_int, c_int64, c_int64, c_int64, c_int, vp, vp, c_size_t]
+    lib.obc_refit_workspace_bytes.argtypes = [c_int, c_int, sp]
+    lib.obc_refit.argtypes = [vp, vp, c_int, vp, c_int, vp, c_int, vp, c_size_t]
     lib.obc_global_select_workspace_bytes.argtypes = [c_int, c_int, sp]
     lib.obc_global_select.argtypes = [vp, vp, vp, c_int, c_int, c_int64, vp, vp, vp, c_size_t]
     lib.obc_gather_trace.argtypes = [vp, vp, vp, vp, c_int, c_int, c_int, vp]
@@ -176,6 +181,38 @@ class Context:
         ws = self.workspace(need.value)
         self._ck(self.lib.obc_invert(self.h, _ptr(H, torch.float32), d, c_void_p(ws.data_ptr()), ws.numel()))
         return H
+
+    def obc_cross(self, X, Y, C=None, accumulate=False):
+        d_col, N = X.shape
+        d_row, Ny = Y.shape
+        if Ny != N:
+            raise ValueError("X and Y must hold the same number of samples")
+        if X.stride(1) != 1 or Y.stride(1) != 1:
+            raise ValueError("X and Y must have unit stride along the sample axis")
+        if C is None:
+            C = torch.empty(d_row, d_col, dtype=torch.float32, device=X.device)
+        need = c_size_t()
+        self.lib.obc_cross_workspace_bytes(d_row, d_col, N, byref(need))
+        ws = self.workspace(need.value)
+        self._ck(self.lib.obc_cross(self.h, c_void_p(X.data_ptr()), c_void_p(Y.data_ptr()), d_col, d_row, N,
+                                    X.stride(0), Y.stride(0), int(bool(accumulate)), _ptr(C, torch.float32),
+                                    c_void_p(ws.data_ptr()), ws.numel()))
+        return C
+
+    def obc_refit(self, H, C, invert_in_place=False, W_out=None):
+        d_col = H.shape[0]
+        d_row = C.shape[0]
+        if C.shape[1] != d_col:
+            raise ValueError("C must be d_row x d_col")
+        if W_out is None:
+            W_out = torch.empty(d_row, d_col, dtype=torch.float32, device=H.device)
+        need = c_size_t()
+        self.lib.obc_refit_workspace_bytes(d_col, d_row, byref(need))
+        ws = self.workspace(need.value)
+        self._ck(self.lib.obc_refit(self.h, _ptr(H, torch.float32), d_col, _ptr(C, torch.float32), d_row,
+                                    _ptr(W_out, torch.float32), int(bool(invert_in_place)),
+                                    c_void_p(ws.data_ptr()), ws.numel()))
+        return W_out
 
     def rows_workspace_bytes(self, R, d, strategy=STRATEGY_AUTO):
         need = c_size_t()

@@ -1,4 +1,6 @@
-// obc_hessian: H = 2 X X^T (+ dampening), Sec. 4 of arxiv 2208.11580.
+// obc_hessian: H = 2 X X^T (+ dampening), Sec. 4 of arxiv 2208.11580, and obc_cross: 2 Y X^T, the
+// second moment that the sequential variant (appendix "Sequential Quantization with OBQ")
+// accumulates beside it.
 //
 // A dense symmetric rank-N contraction, so it runs on the fp32 matrix cores:
 // v_mfma_f32_32x32x2_f32, 128x128 output tiles per 256-thread workgroup (four waves, each
@@ -20,11 +22,10 @@ constexpr int LDT = BM + 4;   // padded LDS row
 
 __host__ __device__ inline int tiles_of(int d) { return (d + BM - 1) / BM; }
 
-// How many slices of the sample axis, and how long each is (multiple of BK).
-inline void split_plan(int d, int64_t N, int *S, int64_t *kchunk)
+// How many slices of the sample axis, and how long each is (multiple of BK), for a launch of
+// `ntri` output tiles.
+inline void split_plan_tiles(int64_t ntri, int64_t N, int *S, int64_t *kchunk)
 {
-    int nt = tiles_of(d);
-    int64_t ntri = (int64_t)nt * (nt + 1) / 2;
     int64_t s = (1024 + ntri - 1) / ntri;
     int64_t smax = (N + 2047) / 2048;
     if (s > smax) s = smax;
@@ -38,19 +39,39 @@ inline void split_plan(int d, int64_t N, int *S, int64_t *kchunk)
     *kchunk = kc;
 }
 
-__global__ __launch_bounds__(256) void syrk_partial_kernel(const float *__restrict__ X, int d,
-                                                           int64_t N, int64_t ldx, int64_t kchunk,
-                                                           float *__restrict__ partial, int vec_ok)
+inline void split_plan(int d, int64_t N, int *S, int64_t *kchunk)
+{
+    int nt = tiles_of(d);
+    split_plan_tiles((int64_t)nt * (nt + 1) / 2, N, S, kchunk);
+}
+
+// One slice of P = Ya Xb^T over the samples [kbeg, kend): Ya is da x N (leading dimension lda),
+// Xb is db x N (ldb).  SYM: Ya and Xb are the same matrix and only the tiles on or above the block
+// diagonal are formed.
+template <bool SYM>
+__global__ __launch_bounds__(256) void nt_partial_kernel(const float *__restrict__ Ya, int da,
+                                                         int64_t lda, const float *__restrict__ Xb,
+                                                         int db, int64_t ldb, int64_t N,
+                                                         int64_t kchunk, float *__restrict__ partial,
+                                                         int vec_ok)
 {
     __shared__ float As[BK][LDT];
     __shared__ float Bs[BK][LDT];
 
-    // upper-triangular tile enumeration: blockIdx.x -> (ti <= tj)
-    const int nt = tiles_of(d);
-    int t = blockIdx.x, ti = 0, rowlen = nt;
-    while (t >= rowlen) { t -= rowlen; ++ti; --rowlen; }
-    const int tj = ti + t;
-    const bool on_diag = (ti == tj);
+    int ti, tj;
+    if (SYM) {
+        // upper-triangular tile enumeration: blockIdx.x -> (ti <= tj)
+        const int nt = tiles_of(da);
+        int t = blockIdx.x, rowlen = nt;
+        ti = 0;
+        while (t >= rowlen) { t -= rowlen; ++ti; --rowlen; }
+        tj = ti + t;
+    } else {
+        const int ntb = tiles_of(db);
+        ti = blockIdx.x / ntb;
+        tj = blockIdx.x % ntb;
+    }
+    const bool on_diag = SYM && (ti == tj);
 
     const int64_t kbeg = (int64_t)blockIdx.y * kchunk;
     const int64_t kend = (kbeg + kchunk < N) ? kbeg + kchunk : N;
@@ -68,15 +89,15 @@ __global__ __launch_bounds__(256) void syrk_partial_kernel(const float *__restri
 
     // loader: a 128 x 16 slab is 512 float4; thread takes quads tid and tid + 256
     float4 ra[2], rb[2];
-    auto fetch = [&](int tile, int64_t k0, float4(&r)[2]) {
+    auto fetch = [&](const float *M, int rows, int64_t ld, int tile, int64_t k0, float4(&r)[2]) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             int f = tid + h * 256;
             int row = tile * BM + (f >> 2);
             int64_t k = k0 + (f & 3) * 4;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (row < d) {
-                const float *src = X + (int64_t)row * ldx + k;
+            if (row < rows) {
+                const float *src = M + (int64_t)row * ld + k;
                 if (vec_ok && k + 3 < kend) {
                     v = *reinterpret_cast<const float4 *>(src);
                 } else {
@@ -102,16 +123,16 @@ __global__ __launch_bounds__(256) void syrk_partial_kernel(const float *__restri
     };
 
     if (kbeg < kend) {
-        fetch(ti, kbeg, ra);
-        if (!on_diag) fetch(tj, kbeg, rb);
+        fetch(Ya, da, lda, ti, kbeg, ra);
+        if (!on_diag) fetch(Xb, db, ldb, tj, kbeg, rb);
     }
     for (int64_t k0 = kbeg; k0 < kend; k0 += BK) {
         stash(As, ra);
         if (!on_diag) stash(Bs, rb);
         __syncthreads();
         if (k0 + BK < kend) {
-            fetch(ti, k0 + BK, ra);
-            if (!on_diag) fetch(tj, k0 + BK, rb);
+            fetch(Ya, da, lda, ti, k0 + BK, ra);
+            if (!on_diag) fetch(Xb, db, ldb, tj, k0 + BK, rb);
         }
         const float(*Bt)[LDT] = on_diag ? As : Bs;
         const int kl = lane >> 5, il = lane & 31;
@@ -131,7 +152,7 @@ __global__ __launch_bounds__(256) void syrk_partial_kernel(const float *__restri
 
     // accumulator layout of the 32x32 MFMA: lane holds column (lane % 32) and, for register v,
     // row 8 * (v / 4) + 4 * (lane / 32) + v % 4
-    float *out = partial + (int64_t)blockIdx.y * d * d;
+    float *out = partial + (int64_t)blockIdx.y * da * db;
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -140,7 +161,7 @@ __global__ __launch_bounds__(256) void syrk_partial_kernel(const float *__restri
             for (int v = 0; v < 16; ++v) {
                 int i = ti * BM + wm * 64 + a * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                 int j = tj * BM + wn * 64 + b * 32 + (lane & 31);
-                if (i < d && j < d) out[(int64_t)i * d + j] = acc[a][b][v];
+                if (i < da && j < db) out[(int64_t)i * db + j] = acc[a][b][v];
             }
 }
 
@@ -157,6 +178,18 @@ __global__ __launch_bounds__(256) void syrk_reduce_kernel(const float *__restric
     for (int k = 0; k < S; ++k) s += partial[(int64_t)k * d * d + src];
     s *= 2.f;
     H[e] = accumulate ? H[e] + s : s;
+}
+
+// C[e] (+)= 2 * sum_s partial[s][e] over a dense da x db result, slices added in index order.
+__global__ __launch_bounds__(256) void nt_reduce_kernel(const float *__restrict__ partial, int S,
+                                                        int64_t n, int accumulate, float *__restrict__ C)
+{
+    int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n) return;
+    float s = 0.f;
+    for (int k = 0; k < S; ++k) s += partial[(int64_t)k * n + e];
+    s *= 2.f;
+    C[e] = accumulate ? C[e] + s : s;
 }
 
 // diag(H) += damp_rel * mean(diag(H)); one workgroup, fixed-order tree sum in fp64.
@@ -209,8 +242,8 @@ int obc_hessian(obc_ctx *ctx, const float *X, int d, int64_t N, int64_t ldx, flo
     const int vec_ok = (ldx % 4 == 0) && (((uintptr_t)X & 15) == 0);
     float *partial = (float *)ws;
 
-    syrk_partial_kernel<<<dim3(ntri, S), 256, 0, ctx->stream>>>(X, d, N, ldx, kchunk, partial, vec_ok);
-    OBC_LAUNCH_CHECK(ctx, "syrk_partial_kernel");
+    nt_partial_kernel<true><<<dim3(ntri, S), 256, 0, ctx->stream>>>(X, d, ldx, X, d, ldx, N, kchunk, partial, vec_ok);
+    OBC_LAUNCH_CHECK(ctx, "nt_partial_kernel");
     const int64_t n = (int64_t)d * d;
     syrk_reduce_kernel<<<(unsigned)((n + 255) / 256), 256, 0, ctx->stream>>>(partial, S, d, accumulate, H);
     OBC_LAUNCH_CHECK(ctx, "syrk_reduce_kernel");
@@ -218,6 +251,50 @@ int obc_hessian(obc_ctx *ctx, const float *X, int d, int64_t N, int64_t ldx, flo
         dampen_kernel<<<1, 1024, 0, ctx->stream>>>(H, d, damp_rel);
         OBC_LAUNCH_CHECK(ctx, "dampen_kernel");
     }
+    return OBC_OK;
+}
+
+static void cross_plan(int d_row, int d_col, int64_t N, int *S, int64_t *kchunk)
+{
+    split_plan_tiles((int64_t)tiles_of(d_row) * tiles_of(d_col), N, S, kchunk);
+}
+
+int obc_cross_workspace_bytes(int d_row, int d_col, int64_t N, size_t *bytes)
+{
+    if (!bytes || d_row <= 0 || d_col <= 0 || N < 0) return OBC_ERR_BAD_ARG;
+    int S;
+    int64_t kc;
+    cross_plan(d_row, d_col, N > 0 ? N : 1, &S, &kc);
+    *bytes = obc_align_up((size_t)S * d_row * d_col * sizeof(float), 256);
+    return OBC_OK;
+}
+
+int obc_cross(obc_ctx *ctx, const float *X, const float *Y, int d_col, int d_row, int64_t N, int64_t ldx,
+              int64_t ldy, int accumulate, float *C, void *ws, size_t ws_bytes)
+{
+    if (!ctx) return OBC_ERR_BAD_ARG;
+    if (!X || !Y || !C) return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_cross: null X, Y or C");
+    if (d_col <= 0 || d_row <= 0 || N <= 0)
+        return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_cross: d_col, d_row and N must be positive");
+    if (ldx < N || ldy < N)
+        return obc_fail(ctx, OBC_ERR_BAD_SHAPE, "obc_cross: ldx (%lld) or ldy (%lld) < N (%lld)", (long long)ldx,
+                        (long long)ldy, (long long)N);
+    size_t need;
+    obc_cross_workspace_bytes(d_row, d_col, N, &need);
+    if (!ws || ws_bytes < need)
+        return obc_fail(ctx, OBC_ERR_WORKSPACE, "obc_cross: workspace of %zu bytes needed, %zu given", need, ws_bytes);
+
+    int S;
+    int64_t kchunk;
+    cross_plan(d_row, d_col, N, &S, &kchunk);
+    const int ntiles = tiles_of(d_row) * tiles_of(d_col);
+    const int vec_ok = (ldx % 4 == 0) && (ldy % 4 == 0) && (((uintptr_t)X & 15) == 0) && (((uintptr_t)Y & 15) == 0);
+    float *partial = (float *)ws;
+    nt_partial_kernel<false><<<dim3(ntiles, S), 256, 0, ctx->stream>>>(Y, d_row, ldy, X, d_col, ldx, N, kchunk, partial, vec_ok);
+    OBC_LAUNCH_CHECK(ctx, "nt_partial_kernel");
+    const int64_t n = (int64_t)d_row * d_col;
+    nt_reduce_kernel<<<(unsigned)((n + 255) / 256), 256, 0, ctx->stream>>>(partial, S, n, accumulate, C);
+    OBC_LAUNCH_CHECK(ctx, "nt_reduce_kernel");
     return OBC_OK;
 }
 

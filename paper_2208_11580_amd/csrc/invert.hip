@@ -28,6 +28,12 @@ __global__ void f32_to_f64_kernel(const float *__restrict__ src, double *__restr
     if (e < n) dst[e] = (double)src[e];
 }
 
+__global__ void f64_to_f32_kernel(const double *__restrict__ src, float *__restrict__ dst, int64_t n)
+{
+    int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < n) dst[e] = (float)src[e];
+}
+
 __device__ __forceinline__ double readlane_f64(double v, int l)
 {
     long long b = __double_as_longlong(v);
@@ -235,16 +241,25 @@ int obc_invert_workspace_bytes(int d, size_t *bytes)
     return OBC_OK;
 }
 
-int obc_invert(obc_ctx *ctx, float *H, int d, void *ws, size_t ws_bytes)
-{
-    if (!ctx) return OBC_ERR_BAD_ARG;
-    if (!H) return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_invert: null matrix");
-    if (d <= 0) return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_invert: d must be positive");
-    size_t need;
-    obc_invert_workspace_bytes(d, &need);
-    if (!ws || ws_bytes < need)
-        return obc_fail(ctx, OBC_ERR_WORKSPACE, "obc_invert: workspace of %zu bytes needed, %zu given", need, ws_bytes);
+}  // extern "C"
 
+namespace {
+
+GemmArgs mk(int M, int N, int K, double alpha, const double *A, int64_t as_i, int64_t as_k, const double *B,
+            int64_t bs_k, int64_t bs_j, double beta, double *C, int64_t ldc, int lower_only, int klo_mode,
+            float *out32)
+{
+    GemmArgs g;
+    g.M = M; g.N = N; g.K = K; g.alpha = alpha; g.A = A; g.as_i = as_i; g.as_k = as_k; g.B = B;
+    g.bs_k = bs_k; g.bs_j = bs_j; g.beta = beta; g.C = C; g.ldc = ldc; g.lower_only = lower_only;
+    g.klo_mode = klo_mode; g.out32 = out32;
+    return g;
+}
+
+// Steps 1 and 2 on the workspace `ws` (laid out as obc_invert_workspace_bytes says): on return
+// *Yout is L^-1 in fp64, lower triangular with exact zeros above the diagonal.
+int factor_inverse(obc_ctx *ctx, const float *H, int d, void *ws, double **Yout)
+{
     hipStream_t st = ctx->stream;
     const int nblk = (d + NB - 1) / NB;
     const size_t mat = obc_align_up((size_t)d * d * sizeof(double), 256);
@@ -258,15 +273,6 @@ int obc_invert(obc_ctx *ctx, float *H, int d, void *ws, size_t ws_bytes)
     eye_f64_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(Y, d);
     OBC_LAUNCH_CHECK(ctx, "f32_to_f64_kernel");
 
-    auto mk = [](int M, int N, int K, double alpha, const double *A, int64_t as_i, int64_t as_k,
-                 const double *B, int64_t bs_k, int64_t bs_j, double beta, double *C, int64_t ldc,
-                 int lower_only, int klo_mode, float *out32) {
-        GemmArgs g;
-        g.M = M; g.N = N; g.K = K; g.alpha = alpha; g.A = A; g.as_i = as_i; g.as_k = as_k; g.B = B;
-        g.bs_k = bs_k; g.bs_j = bs_j; g.beta = beta; g.C = C; g.ldc = ldc; g.lower_only = lower_only;
-        g.klo_mode = klo_mode; g.out32 = out32;
-        return g;
-    };
     auto dual_grid = [](const GemmArgs &a, const GemmArgs &b) {
         unsigned gx = (unsigned)((((a.N > b.N) ? a.N : b.N) + NB - 1) / NB);
         unsigned gy = (unsigned)((((a.M > b.M) ? a.M : b.M) + NB - 1) / NB);
@@ -303,11 +309,78 @@ int obc_invert(obc_ctx *ctx, float *H, int d, void *ws, size_t ws_bytes)
         }
     }
     OBC_LAUNCH_CHECK(ctx, "factorisation kernels");
+    *Yout = Y;
+    return OBC_OK;
+}
 
-    // 3. H^-1 = Y^T Y, rounded to fp32, mirrored
-    gemm64_kernel<<<grid64(d, d), 256, 0, st>>>(mk(d, d, d, 1.0, Y, 1, d, Y, d, 1, 0.0, nullptr, d, 1, 2, H));
+// 3. H^-1 = Y^T Y, rounded to fp32, mirrored
+int inverse_from_factor(obc_ctx *ctx, const double *Y, int d, float *H)
+{
+    gemm64_kernel<<<grid64(d, d), 256, 0, ctx->stream>>>(mk(d, d, d, 1.0, Y, 1, d, Y, d, 1, 0.0, nullptr, d, 1, 2, H));
     OBC_LAUNCH_CHECK(ctx, "gemm64_kernel");
+    return OBC_OK;
+}
 
+}  // namespace
+
+extern "C" {
+
+int obc_invert(obc_ctx *ctx, float *H, int d, void *ws, size_t ws_bytes)
+{
+    if (!ctx) return OBC_ERR_BAD_ARG;
+    if (!H) return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_invert: null matrix");
+    if (d <= 0) return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_invert: d must be positive");
+    size_t need;
+    obc_invert_workspace_bytes(d, &need);
+    if (!ws || ws_bytes < need)
+        return obc_fail(ctx, OBC_ERR_WORKSPACE, "obc_invert: workspace of %zu bytes needed, %zu given", need, ws_bytes);
+    double *Y;
+    int rc = factor_inverse(ctx, H, d, ws, &Y);
+    if (rc != OBC_OK) return rc;
+    rc = inverse_from_factor(ctx, Y, d, H);
+    if (rc != OBC_OK) return rc;
+    return obc_check(ctx);
+}
+
+int obc_refit_workspace_bytes(int d_col, int d_row, size_t *bytes)
+{
+    if (!bytes || d_col <= 0 || d_row <= 0) return OBC_ERR_BAD_ARG;
+    size_t inv;
+    obc_invert_workspace_bytes(d_col, &inv);
+    *bytes = inv + 2 * obc_align_up((size_t)d_row * d_col * sizeof(double), 256);
+    return OBC_OK;
+}
+
+int obc_refit(obc_ctx *ctx, float *H, int d_col, const float *C, int d_row, float *W_out,
+              int invert_in_place, void *ws, size_t ws_bytes)
+{
+    if (!ctx) return OBC_ERR_BAD_ARG;
+    if (!H || !C || !W_out) return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_refit: null H, C or W_out");
+    if (d_col <= 0 || d_row <= 0) return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_refit: d_col and d_row must be positive");
+    size_t need, inv;
+    obc_refit_workspace_bytes(d_col, d_row, &need);
+    obc_invert_workspace_bytes(d_col, &inv);
+    if (!ws || ws_bytes < need)
+        return obc_fail(ctx, OBC_ERR_WORKSPACE, "obc_refit: workspace of %zu bytes needed, %zu given", need, ws_bytes);
+    hipStream_t st = ctx->stream;
+    const int d = d_col, R = d_row;
+    double *Y;
+    int rc = factor_inverse(ctx, H, d, ws, &Y);
+    if (rc != OBC_OK) return rc;
+    const size_t rd = obc_align_up((size_t)R * d * sizeof(double), 256);
+    double *C64 = (double *)((char *)ws + inv);
+    double *T1 = (double *)((char *)ws + inv + rd);
+    const int64_t n = (int64_t)R * d;
+    f32_to_f64_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(C, C64, n);
+    // W = C H^-1 = (C Y^T) Y with Y = L^-1: both products in fp64
+    gemm64_kernel<<<grid64(R, d), 256, 0, st>>>(mk(R, d, d, 1.0, C64, d, 1, Y, 1, d, 0.0, T1, d, 0, 0, nullptr));
+    gemm64_kernel<<<grid64(R, d), 256, 0, st>>>(mk(R, d, d, 1.0, T1, d, 1, Y, d, 1, 0.0, C64, d, 0, 1, nullptr));
+    f64_to_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(C64, W_out, n);
+    OBC_LAUNCH_CHECK(ctx, "refit kernels");
+    if (invert_in_place) {
+        rc = inverse_from_factor(ctx, Y, d, H);
+        if (rc != OBC_OK) return rc;
+    }
     return obc_check(ctx);
 }
 

@@ -89,6 +89,68 @@ def test_invert_reports_non_spd(obc):
     obc.obc_check()  # latch is cleared
 
 
+# ------------------------------------------------------------------------------ sequential re-fit
+@pytest.mark.parametrize("d_col,d_row,N,pad", [(32, 16, 256, 0), (200, 77, 3001, 3), (131, 300, 777, 1),
+                                               (576, 64, 20000, 0)])
+def test_cross_matches_oracle(obc, orc, d_col, d_row, N, pad):
+    torch.manual_seed(d_col + d_row)
+    Xf = torch.randn(d_col, N + pad, device="cuda")
+    Yf = torch.randn(d_row, N + 2 * pad, device="cuda") + 0.3 * Xf[:1, :N].mean()
+    X, Y = Xf[:, :N], Yf[:, :N]
+    C = obc.obc_cross(X, Y)
+    ref = orc.cross(_np(X), _np(Y))
+    assert C.shape == (d_row, d_col)
+    assert np.linalg.norm(_np(C) - ref) / np.linalg.norm(ref) < 2e-6
+    assert np.allclose(_np(C), ref, rtol=0, atol=3e-6 * np.abs(ref).max())
+    # accumulated in two batches
+    h = N // 2
+    Cacc = obc.obc_cross(Xf[:, :h], Yf[:, :h])
+    Cacc = obc.obc_cross(Xf[:, h:N], Yf[:, h:N], C=Cacc, accumulate=True)
+    assert np.linalg.norm(_np(Cacc) - ref) / np.linalg.norm(ref) < 2e-6
+
+
+@pytest.mark.parametrize("d_col,d_row", [(32, 16), (203, 70), (576, 64), (257, 1)])
+def test_refit_matches_oracle(obc, orc, d_col, d_row):
+    # appendix "Sequential Quantization with OBQ": inputs of the compressed model (here the dense
+    # inputs plus a perturbation), outputs of the dense layer
+    W, X = _layer("conv64x576", d_col=d_col, d_row=d_row, n_samples=4 * d_col + 50)
+    torch.manual_seed(3)
+    Xc = (X + 0.1 * X.std() * torch.randn_like(X)).contiguous()
+    Y = (W.double() @ X.double()).float()
+    H = obc.obc_hessian(Xc)
+    C = obc.obc_cross(Xc, Y)
+    H0 = H.clone()
+    Wr = obc.obc_refit(H, C)
+    assert torch.equal(H, H0)                     # H is left alone
+    ref = orc.refit(_np(H).astype(np.float64), _np(C).astype(np.float64))
+    err = np.linalg.norm(_np(Wr) - ref) / np.linalg.norm(ref)
+    assert err < 1e-6, err
+    # sharing the factorisation: same weights, and H becomes what obc_invert gives
+    Wr2 = obc.obc_refit(H, C, invert_in_place=True)
+    assert torch.equal(Wr, Wr2)
+    assert torch.equal(H, obc.obc_invert(H0.clone()))
+    # the re-fitted weights have (up to the fp32 rounding of H, C and W) zero gradient under the
+    # new inputs, the gradient being written out from the data in fp64
+    Wn, Xn, Yn = _np(Wr).astype(np.float64), _np(Xc).astype(np.float64), _np(Y).astype(np.float64)
+    lam = 0.01 * np.mean(2.0 * np.sum(Xn * Xn, axis=1))
+    grad = 2.0 * (Wn @ Xn - Yn) @ Xn.T + lam * Wn
+    scale = np.linalg.norm(2.0 * Yn @ Xn.T)
+    assert np.linalg.norm(grad) < 5e-4 * scale
+
+
+def test_sequential_obq_flow(obc, orc):
+    # re-fit, then OBQ on the re-fitted weights with the same Hessian, as the appendix describes;
+    # each stage is compared with the oracle fed the GPU's previous stage
+    W, X = _layer("conv64x576", d_col=260, d_row=6, n_samples=3000)
+    torch.manual_seed(4)
+    Xc = (X + 0.2 * X.std() * torch.randn_like(X)).contiguous()
+    Y = (W.double() @ X.double()).float()
+    H = obc.obc_hessian(Xc)
+    C = obc.obc_cross(Xc, Y)
+    Wr = obc.obc_refit(H, C, invert_in_place=True)      # H now holds the inverse
+    _check_quant(obc, orc, Wr, H, 3, 0)
+
+
 # ------------------------------------------------------------------------------ pruning rows
 def _check_prune(obc, orc, W, Hinv, k_steps, nm, strategy, rows=None, want_trace=False):
     res = obc.obc_prune_rows(W, Hinv, k_steps=k_steps, nm=nm, strategy=strategy, want_trace=want_trace)

@@ -567,3 +567,47 @@ def test_symmetric_grid_is_symmetric_about_zero(orc):
         assert np.isclose(levels[0], -0.31) and np.isclose(levels[-1], 0.31)
         assert np.allclose(levels, -levels[::-1])
     assert orc.symmetric_grid(np.zeros(3), 4) == (1.0, -0.0, 15) or orc.symmetric_grid(np.zeros(3), 4)[0] == 1.0
+
+
+# ----------------------------------------------------------------------------- sequential re-fit
+def test_refit_is_linear_regression(orc):
+    # appendix "Sequential Quantization with OBQ": without dampening the re-fit is the least-squares
+    # solution of W X = Y, here obtained from the library's SVD-based routine on the raw data
+    rng = np.random.default_rng(5)
+    d_col, d_row, n = 12, 5, 60
+    X = rng.standard_normal((d_col, n))
+    Y = rng.standard_normal((d_row, n))
+    W = orc.refit(orc.hessian(X, damp_rel=-1.0), orc.cross(X, Y))
+    ref = np.linalg.lstsq(X.T, Y.T, rcond=None)[0].T
+    assert W.shape == (d_row, d_col)
+    assert np.allclose(W, ref, rtol=1e-9, atol=1e-12)
+    # stationarity: the residual is orthogonal to every input feature
+    assert np.allclose((W @ X - Y) @ X.T, 0.0, atol=1e-9)
+
+
+def test_refit_recovers_weights_of_a_noise_free_layer(orc):
+    rng = np.random.default_rng(6)
+    d_col, d_row, n = 10, 4, 40
+    X = rng.standard_normal((d_col, n))
+    W0 = rng.standard_normal((d_row, d_col))
+    W = orc.refit(orc.hessian(X, damp_rel=-1.0), orc.cross(X, W0 @ X))
+    assert np.allclose(W, W0, rtol=1e-9, atol=1e-11)
+
+
+def test_dampened_refit_zeroes_the_gradient_of_the_dampened_quadratic(orc):
+    # with H = 2 X X^T + lam I the re-fit minimises ||W X - Y||^2 + lam/2 ||W||^2, whose gradient
+    # 2 (W X - Y) X^T + lam W is written out here from the data
+    rng = np.random.default_rng(7)
+    d_col, d_row, n = 9, 3, 30
+    X = rng.standard_normal((d_col, n))
+    Y = rng.standard_normal((d_row, n))
+    H = orc.hessian(X, damp_rel=0.05)
+    lam = 0.05 * np.mean(2.0 * np.sum(X * X, axis=1))
+    W = orc.refit(H, orc.cross(X, Y))
+    grad = 2.0 * (W @ X - Y) @ X.T + lam * W
+    assert np.allclose(grad, 0.0, atol=1e-9)
+    # and it is a minimum: any perturbation raises the objective
+    def obj(V):
+        return np.sum((V @ X - Y) ** 2) + 0.5 * lam * np.sum(V * V)
+    for _ in range(5):
+        assert obj(W + 1e-3 * rng.standard_normal(W.shape)) > obj(W)
