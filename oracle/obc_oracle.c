@@ -12,6 +12,7 @@
  *   - Sec. 4 "N:M Sparsity"          : eligibility filter in the same loop
  *   - Sec. 5 eq. (7), Appendix Alg. 3: quantize one row (orc_row_solve, mode 1)
  *   - Lemma 1                        : the rank-1 row/column removal inside the loop
+ *   - Sec. 4 "Block-Sparsity", eq. (5): prune one row in blocks of c (orc_block_row_solve)
  *   - Appendix Algorithm 2           : global mask selection (orc_global_select)
  *   - Sec. 4 "Implementation Details": inverse of the dampened Hessian (orc_spd_inverse)
  *
@@ -223,6 +224,159 @@ int orc_row_solve(int mode, const double *Hinv, int d, const double *w_in, int k
     }
     free(blk_pruned);
     return rc;
+}
+
+/* Solve the c x c symmetric positive definite system M z = b by Gaussian elimination without
+ * pivoting (M, b are overwritten; z returned in b).  Returns 0, or ORC_NUMERIC on a bad pivot. */
+static int orc_small_solve(double *M, double *b, int c)
+{
+    for (int k = 0; k < c; ++k) {
+        double piv = M[k * c + k];
+        if (!(piv > 0.0) || !isfinite(piv)) return ORC_NUMERIC;
+        for (int i = k + 1; i < c; ++i) {
+            double f = M[i * c + k] / piv;
+            for (int j = k; j < c; ++j) M[i * c + j] -= f * M[k * c + j];
+            b[i] -= f * b[k];
+        }
+    }
+    for (int k = c - 1; k >= 0; --k) {
+        double v = b[k];
+        for (int j = k + 1; j < c; ++j) v -= M[k * c + j] * b[j];
+        b[k] = v / M[k * c + k];
+    }
+    return ORC_OK;
+}
+
+/* ---------------------------------------------------------------------------
+ * One row of the block-pruning variant (Sec. 4 "Block-Sparsity", eq. (5)): Algorithm 1 on
+ * blocks P of c consecutive indices (block b = indices b c .. b c + c - 1; d must be a
+ * multiple of c).  Per step: the live block with the smallest w_P^T ((H^-1)_P)^-1 w_P is
+ * chosen (ties to the lowest block), all weights move by -H^-1[:,P] ((H^-1)_P)^-1 w_P (the
+ * block itself to exactly zero), and the block's indices are removed from the inverse one
+ * after another with Lemma 1, in ascending order.
+ *
+ *   c         block size (1 <= c <= 16); c = 1 is Algorithm 1
+ *   k_blocks  number of steps (<= d / c)
+ *   forced    nullable: block index to take at each step
+ *   order     out, k_blocks: chosen block per step
+ *   loss      out, k_blocks: w_P^T ((H^-1)_P)^-1 w_P / 2 (the 1/2 as for single weights)
+ *   w_out     out, d;  trace out, nullable, k_blocks x d
+ *   min_score / pick_score out, nullable, k_blocks (scores without the 1/2)
+ *   A         scratch d x d;  live scratch d bytes
+ * ------------------------------------------------------------------------- */
+int orc_block_row_solve(const double *Hinv, int d, const double *w_in, int c, int k_blocks,
+                        const int32_t *forced, int32_t *order, double *loss, double *w_out,
+                        double *trace, double *min_score, double *pick_score, double *A,
+                        uint8_t *live)
+{
+    if (!Hinv || !w_in || !order || !loss || !w_out || !A || !live) return ORC_BAD_ARG;
+    if (d <= 0 || c < 1 || c > 16 || d % c != 0) return ORC_BAD_ARG;
+    int nb = d / c;
+    if (k_blocks < 0 || k_blocks > nb) return ORC_BAD_ARG;
+    double *w = w_out;
+    memcpy(A, Hinv, (size_t)d * d * sizeof(double));
+    memcpy(w, w_in, (size_t)d * sizeof(double));
+    for (int j = 0; j < d; ++j) live[j] = 1;
+    double M[16 * 16], z[16];
+
+    for (int t = 0; t < k_blocks; ++t) {
+        int best = -1;
+        double best_s = 0.0;
+        for (int b = 0; b < nb; ++b) {
+            if (!live[b * c]) continue;
+            for (int i = 0; i < c; ++i) {
+                for (int j = 0; j < c; ++j) M[i * c + j] = A[(size_t)(b * c + i) * d + (b * c + j)];
+                z[i] = w[b * c + i];
+            }
+            if (orc_small_solve(M, z, c) != ORC_OK) return ORC_NUMERIC;
+            double s = 0.0;
+            for (int i = 0; i < c; ++i) s += w[b * c + i] * z[i];
+            if (best < 0 || s < best_s) { best = b; best_s = s; }
+        }
+        if (best < 0) return ORC_BAD_ARG;
+        int bp = best;
+        if (forced) {
+            bp = forced[t];
+            if (bp < 0 || bp >= nb || !live[bp * c]) return ORC_BAD_ARG;
+        }
+        /* z = ((H^-1)_P)^-1 w_P for the block taken */
+        for (int i = 0; i < c; ++i) {
+            for (int j = 0; j < c; ++j) M[i * c + j] = A[(size_t)(bp * c + i) * d + (bp * c + j)];
+            z[i] = w[bp * c + i];
+        }
+        if (orc_small_solve(M, z, c) != ORC_OK) return ORC_NUMERIC;
+        double s = 0.0;
+        for (int i = 0; i < c; ++i) s += w[bp * c + i] * z[i];
+        if (min_score) min_score[t] = best_s;
+        if (pick_score) pick_score[t] = s;
+        order[t] = bp;
+        loss[t] = 0.5 * s;
+
+        /* weight update: w <- w - H^-1[:,P] z on the live set, the block itself to zero */
+        for (int j = 0; j < d; ++j) {
+            if (!live[j]) continue;
+            double dj = 0.0;
+            for (int i = 0; i < c; ++i) dj += A[(size_t)j * d + (bp * c + i)] * z[i];
+            w[j] -= dj;
+        }
+        for (int i = 0; i < c; ++i) w[bp * c + i] = 0.0;
+
+        /* Lemma 1 for every index of the block, one after another */
+        for (int q = 0; q < c; ++q) {
+            int p = bp * c + q;
+            double app = A[(size_t)p * d + p];
+            if (!(app > 0.0) || !isfinite(app)) return ORC_NUMERIC;
+            for (int i = 0; i < d; ++i) {
+                if (!live[i] || i == p) continue;
+                double f = A[(size_t)i * d + p] / app;
+                for (int j = 0; j < d; ++j) {
+                    if (!live[j] || j == p) continue;
+                    A[(size_t)i * d + j] -= f * A[(size_t)p * d + j];
+                }
+            }
+            live[p] = 0;
+        }
+        if (trace) memcpy(trace + (size_t)t * d, w, (size_t)d * sizeof(double));
+    }
+    return ORC_OK;
+}
+
+/* Several rows of the block variant over OpenMP threads (arrays stacked along R). */
+int orc_block_rows_solve(const double *Hinv, int R, int d, const double *W, int c, int k_blocks,
+                         int32_t *order, double *loss, double *W_out, int n_threads, int *threads_used)
+{
+    if (R < 0 || d <= 0) return ORC_BAD_ARG;
+    int rc_all = ORC_OK;
+    int used = 1;
+#ifdef _OPENMP
+    if (n_threads > 0) omp_set_num_threads(n_threads);
+#pragma omp parallel
+    {
+#pragma omp single
+        used = omp_get_num_threads();
+    }
+#endif
+#pragma omp parallel
+    {
+        double *A = (double *)malloc((size_t)d * d * sizeof(double));
+        uint8_t *live = (uint8_t *)malloc((size_t)d);
+#pragma omp for schedule(dynamic, 1)
+        for (int i = 0; i < R; ++i) {
+            int rc = (A && live) ? orc_block_row_solve(Hinv, d, W + (size_t)i * d, c, k_blocks, NULL,
+                                                       order + (size_t)i * k_blocks,
+                                                       loss + (size_t)i * k_blocks, W_out + (size_t)i * d,
+                                                       NULL, NULL, NULL, A, live)
+                                : ORC_BAD_ARG;
+            if (rc != ORC_OK) {
+#pragma omp critical
+                if (rc_all == ORC_OK) rc_all = rc;
+            }
+        }
+        free(A);
+        free(live);
+    }
+    if (threads_used) *threads_used = used;
+    return rc_all;
 }
 
 /* ---------------------------------------------------------------------------

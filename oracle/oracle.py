@@ -66,6 +66,11 @@ def _load():
             ip, dp, ip, dp, dp, c_int, POINTER(c_int),
         ]
         lib.orc_rows_solve.restype = c_int
+        lib.orc_block_row_solve.argtypes = [dp, c_int, dp, c_int, c_int, ip, ip, dp, dp, dp, dp, dp, dp, bp]
+        lib.orc_block_row_solve.restype = c_int
+        lib.orc_block_rows_solve.argtypes = [dp, c_int, c_int, dp, c_int, c_int, ip, dp, dp, c_int,
+                                             POINTER(c_int)]
+        lib.orc_block_rows_solve.restype = c_int
         lib.orc_global_select.argtypes = [dp, c_int, c_int, c_int64, ip]
         lib.orc_global_select.restype = c_int
         _lib = lib
@@ -181,6 +186,56 @@ def prune_row(Hinv, w, k_steps=None, nm=(0, 0), forced=None, want_trace=False):
     if k_steps is None:
         k_steps = d if nm[1] == 0 else (d // nm[1]) * (nm[1] - nm[0])
     return _row_solve(0, Hinv, w, k_steps, nm=nm, forced=forced, want_trace=want_trace)
+
+
+def block_prune_row(Hinv, w, c, k_blocks=None, forced=None, want_trace=False):
+    """Block-pruning variant (Sec. 4 "Block-Sparsity", eq. (5)) on one row, blocks of ``c``.
+
+    ``order`` holds block indices, ``loss`` the halved block scores.
+    """
+    Hinv = np.ascontiguousarray(Hinv, dtype=np.float64)
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    d = w.shape[0]
+    assert Hinv.shape == (d, d)
+    if k_blocks is None:
+        k_blocks = d // c
+    r = RowResult()
+    r.order = np.zeros(k_blocks, np.int32)
+    r.loss = np.zeros(k_blocks, np.float64)
+    r.codes = None
+    r.pre_round = None
+    r.w = np.zeros(d, np.float64)
+    r.trace = np.zeros((k_blocks, d), np.float64) if want_trace else None
+    r.min_score = np.zeros(k_blocks, np.float64)
+    r.pick_score = np.zeros(k_blocks, np.float64)
+    r.A = np.zeros((d, d), np.float64)
+    r.live = np.zeros(d, np.uint8)
+    f = None if forced is None else np.ascontiguousarray(forced, dtype=np.int32)
+    if f is not None:
+        assert f.shape[0] >= k_blocks
+    rc = _load().orc_block_row_solve(_d(Hinv), d, _d(w), int(c), int(k_blocks), _i(f), _i(r.order),
+                                     _d(r.loss), _d(r.w), _d(r.trace), _d(r.min_score),
+                                     _d(r.pick_score), _d(r.A), _b(r.live))
+    if rc != ORC_OK:
+        raise OracleError(rc, "orc_block_row_solve")
+    return r
+
+
+def block_prune_rows(Hinv, W, c, k_blocks=None, n_threads=0):
+    Hinv = np.ascontiguousarray(Hinv, dtype=np.float64)
+    W = np.ascontiguousarray(W, dtype=np.float64)
+    R, d = W.shape
+    if k_blocks is None:
+        k_blocks = d // c
+    order = np.zeros((R, k_blocks), np.int32)
+    loss = np.zeros((R, k_blocks), np.float64)
+    W_out = np.zeros((R, d), np.float64)
+    used = c_int(0)
+    rc = _load().orc_block_rows_solve(_d(Hinv), R, d, _d(W), int(c), int(k_blocks), _i(order),
+                                      _d(loss), _d(W_out), int(n_threads), ctypes.byref(used))
+    if rc != ORC_OK:
+        raise OracleError(rc, "orc_block_rows_solve")
+    return dict(order=order, loss=loss, W=W_out, threads=used.value)
 
 
 def minmax_grid(w_live, bits: int):

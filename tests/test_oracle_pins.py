@@ -611,3 +611,109 @@ def test_dampened_refit_zeroes_the_gradient_of_the_dampened_quadratic(orc):
         return np.sum((V @ X - Y) ** 2) + 0.5 * lam * np.sum(V * V)
     for _ in range(5):
         assert obj(W + 1e-3 * rng.standard_normal(W.shape)) > obj(W)
+
+
+# ----------------------------------------------------------------------------- block pruning
+def _block_setup(seed, d, c):
+    W, X = _problem(seed, d)
+    H = 2.0 * X @ X.T
+    H += 0.01 * np.mean(np.diag(H)) * np.eye(d)
+    return W[0], H, np.linalg.inv(H)
+
+
+@pytest.mark.parametrize("c,k", [(2, 3), (4, 2), (4, 4), (8, 1)])
+def test_block_pruned_row_equals_least_squares_on_support(orc, c, k):
+    # Sec. 4 "Block-Sparsity": after k block steps the survivors are the exact minimiser of the
+    # layer's quadratic with the chosen blocks held at zero, and zeros come in aligned blocks
+    d = 16
+    w, H, A = _block_setup(21 + c, d, c)
+    r = orc.block_prune_row(A, w, c, k_blocks=k)
+    P = np.concatenate([np.arange(b * c, b * c + c) for b in r.order])
+    assert len(set(r.order.tolist())) == k
+    assert np.all(r.w[P] == 0.0)
+    ref = _ls_on_support(H, w, P, np.zeros(P.size))
+    assert np.allclose(r.w, ref, rtol=1e-8, atol=1e-11)
+    # the recorded losses add up to the true increase of the quadratic
+    assert np.isclose(r.loss.sum(), _quad(H, r.w, w), rtol=1e-8)
+
+
+def test_block_score_is_the_least_squares_cost_of_removing_the_block(orc):
+    # eq. (5): the first step's choice is the block whose removal (with optimal compensation)
+    # costs least; brute force over all blocks with the constrained least-squares solution
+    d, c = 12, 4
+    for seed in range(4):
+        w, H, A = _block_setup(40 + seed, d, c)
+        costs = []
+        for b in range(d // c):
+            P = np.arange(b * c, b * c + c)
+            costs.append(_quad(H, _ls_on_support(H, w, P, np.zeros(c)), w))
+        r = orc.block_prune_row(A, w, c, k_blocks=1)
+        assert r.order[0] == int(np.argmin(costs))
+        assert np.isclose(r.loss[0], min(costs), rtol=1e-8)
+        assert np.isclose(r.min_score[0], 2.0 * min(costs), rtol=1e-8)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_block_greedy_matches_brute_force_every_step(orc, seed):
+    # every step's choice, not only the first: given the blocks already taken, the next block is
+    # the one with the smallest total least-squares cost increase
+    d, c = 12, 3
+    w, H, A = _block_setup(60 + seed, d, c)
+    r = orc.block_prune_row(A, w, c)
+    taken = []
+    prev = 0.0
+    for t in range(d // c):
+        best, best_cost = None, None
+        for b in range(d // c):
+            if b in taken:
+                continue
+            P = np.concatenate([np.arange(x * c, x * c + c) for x in taken + [b]])
+            cost = _quad(H, _ls_on_support(H, w, P, np.zeros(P.size)), w)
+            if best is None or cost < best_cost:
+                best, best_cost = b, cost
+        assert r.order[t] == best
+        assert np.isclose(r.loss[t], best_cost - prev, rtol=1e-7, atol=1e-12)
+        taken.append(best)
+        prev = best_cost
+
+
+def test_block_size_one_is_algorithm_1(orc):
+    d = 14
+    w, H, A = _block_setup(70, d, 1)
+    a = orc.block_prune_row(A, w, 1, want_trace=True)
+    b = orc.prune_row(A, w, want_trace=True)
+    assert np.array_equal(a.order, b.order)
+    assert np.allclose(a.loss, b.loss, rtol=1e-12)
+    assert np.allclose(a.trace, b.trace, rtol=1e-12, atol=1e-15)
+
+
+def test_block_step_equals_single_steps_over_its_indices(orc):
+    # removing a block at once (eq. (5)) and removing its indices one after another with the
+    # single-weight update (eq. (3)) reach the same weights; the single losses add up to the block's
+    d, c = 16, 4
+    w, H, A = _block_setup(80, d, c)
+    r = orc.block_prune_row(A, w, c, k_blocks=2)
+    forced = np.concatenate([np.arange(b * c, b * c + c) for b in r.order]).astype(np.int32)
+    s = orc.prune_row(A, w, k_steps=2 * c, forced=forced)
+    assert np.allclose(s.w, r.w, rtol=1e-9, atol=1e-13)
+    assert np.allclose(s.loss.reshape(2, c).sum(axis=1), r.loss, rtol=1e-9)
+    # and the reduced inverse agrees on the survivors (Lemma 1 applied in either grouping)
+    S = np.flatnonzero(r.live)
+    assert np.allclose(r.A[np.ix_(S, S)], s.A[np.ix_(S, S)], rtol=1e-9, atol=1e-14)
+    assert np.allclose(r.A[np.ix_(S, S)], np.linalg.inv(H[np.ix_(S, S)]), rtol=1e-7)
+
+
+def test_block_rows_driver_and_argument_checks(orc):
+    d, c = 12, 4
+    W, X = _problem(90, d, R=5)
+    A = np.linalg.inv(2.0 * X @ X.T + 0.1 * np.eye(d))
+    res = orc.block_prune_rows(A, W, c, k_blocks=2, n_threads=2)
+    for i in range(5):
+        r = orc.block_prune_row(A, W[i], c, k_blocks=2)
+        assert np.array_equal(res["order"][i], r.order)
+        assert np.array_equal(res["W"][i], r.w)
+        assert np.array_equal(res["loss"][i], r.loss)
+    with pytest.raises(Exception):
+        orc.block_prune_row(A, W[0], 5)          # d not a multiple of c
+    with pytest.raises(Exception):
+        orc.block_prune_row(A, W[0], 4, k_blocks=4)
