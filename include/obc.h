@@ -123,6 +123,22 @@ int obc_prune_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d
                    int nm_n, int nm_m, const int32_t *stop_counts, int32_t *order, float *loss,
                    float *W_out, float *trace, int strategy, void *ws, size_t ws_bytes);
 
+/* Block pruning (Sec. 4 "Block-Sparsity", eq. (5)): Algorithm 1 on blocks of c consecutive
+ * weights (block b = indices b c .. b c + c - 1; d must be a multiple of c, 1 <= c <= 8).  Each
+ * step takes the live block P with the smallest w_P^T ((H^-1)_P)^-1 w_P, moves the remaining
+ * weights by -H^-1[:,P] ((H^-1)_P)^-1 w_P and removes P from the inverse (Lemma 1 for every p in
+ * P).  Arguments as obc_prune_rows, counted in blocks:
+ *   k_blocks     steps per row (<= d / c); stop_counts nullable, per-row step limits in blocks
+ *   order, loss  R x k_blocks out: block index per step and its loss change
+ *                w_P^T ((H^-1)_P)^-1 w_P / 2
+ *   trace        nullable, R x k_blocks x d out: the row after every block step
+ * The traces feed obc_global_select (with d := k_blocks) and obc_gather_trace unchanged.
+ * Workspace: obc_rows_workspace_bytes(R, d, OBC_STRATEGY_RANK1).  strategy: OBC_STRATEGY_AUTO or
+ * OBC_STRATEGY_RANK1. */
+int obc_prune_blocks(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d, int c, int k_blocks,
+                     const int32_t *stop_counts, int32_t *order, float *loss, float *W_out, float *trace,
+                     int strategy, void *ws, size_t ws_bytes);
+
 /* Flags of obc_quant_rows. */
 #define OBC_QUANT_OUTLIERS 1   /* Sec. 5 "Quantization Outliers": while any live weight of the row has
                                   a quantization error |q(w) - w| > delta / 2, the greedy choice runs

@@ -119,6 +119,30 @@ int obc_prune_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d
                           nullptr, 0, nullptr, 0, order, loss, nullptr, W_out, trace, k_steps, ws, ws_bytes);
 }
 
+int obc_prune_blocks(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d, int c, int k_blocks,
+                     const int32_t *stop_counts, int32_t *order, float *loss, float *W_out, float *trace,
+                     int strategy, void *ws, size_t ws_bytes)
+{
+    if (!ctx) return OBC_ERR_BAD_ARG;
+    if (R < 0 || d <= 0 || k_blocks < 0)
+        return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_prune_blocks: negative size");
+    if (c < 1 || c > 8)
+        return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_prune_blocks: block size %d outside 1..8", c);
+    if (d % c != 0)
+        return obc_fail(ctx, OBC_ERR_BAD_SHAPE, "obc_prune_blocks: d (%d) is not a multiple of the block size (%d)", d, c);
+    if (k_blocks > d / c)
+        return obc_fail(ctx, OBC_ERR_BAD_SHAPE, "obc_prune_blocks: k_blocks (%d) > d / c (%d)", k_blocks, d / c);
+    if (R > 0 && (!W || !Hinv || !W_out || (k_blocks > 0 && (!order || !loss))))
+        return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_prune_blocks: null W, Hinv, order, loss or W_out");
+    if (strategy < OBC_STRATEGY_AUTO || strategy > OBC_STRATEGY_BLOCKED)
+        return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_prune_blocks: unknown strategy %d", strategy);
+    if (strategy == OBC_STRATEGY_BLOCKED)
+        return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_prune_blocks: the deferred-update solver does not do block pruning");
+    if (R == 0) return OBC_OK;
+    return rank1_launch(ctx, MODE_BLOCK, W, Hinv, R, d, k_blocks, 0, c, stop_counts, nullptr, nullptr, 0,
+                        nullptr, 0, order, loss, nullptr, W_out, trace, k_blocks, ws, ws_bytes);
+}
+
 int obc_quant_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d,
                    const float *delta, const float *offset, int maxq, const uint8_t *live, int flags,
                    int32_t *order, float *loss, int32_t *codes, float *W_out, int strategy,

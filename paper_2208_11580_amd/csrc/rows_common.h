@@ -9,6 +9,7 @@ namespace obc_rows {
 
 constexpr int MODE_PRUNE = 0;
 constexpr int MODE_QUANT = 1;
+constexpr int MODE_BLOCK = 2;   // pruning in blocks of c consecutive weights (Sec. 4 "Block-Sparsity")
 
 struct Cand {
     float s;   // score; +inf when the thread saw no candidate

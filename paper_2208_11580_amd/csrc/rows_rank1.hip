@@ -13,6 +13,12 @@
 // to column p, A stays symmetric -- is staged in LDS; (3) w and the maintained diagonal are
 // updated; (4) A[i,:] -= (A[i,p] / A_pp) A[p,:] for the live rows i.  Eliminated rows are never
 // read or written again; eliminated columns of live rows are updated but never read.
+//
+// Block pruning (Sec. 4 "Block-Sparsity", eq. (5)) runs in the same loop: every c-th step chooses
+// a block by its score w_P^T ((H^-1)_P)^-1 w_P -- evaluated per candidate block as the sum of the
+// c single-weight scores met when the block's indices are eliminated one after another inside a
+// c x c copy -- and the next c steps take the block's indices in ascending order.  c single
+// eliminations with the single-weight update give exactly the block update of eq. (5).
 #include "rows_common.h"
 
 namespace {
@@ -30,6 +36,7 @@ struct Rank1Args {
     int maxq;
     const uint8_t *live_in;
     int outliers;            // OBQ: restrict the choice to outliers while there are any
+    int blk_c;               // block pruning: block size (0 otherwise)
     int32_t *order;
     float *loss;
     int32_t *codes;
@@ -39,7 +46,48 @@ struct Rank1Args {
     int *status;
 };
 
-template <int MODE>
+// Score of one block for block pruning: v^T M^-1 v for the block's weights v and its c x c
+// diagonal block M of the current inverse (diagonal from the fp64 copy, the rest from A), as
+// the sum of v_k^2 / M_kk over a Gaussian elimination of the block.  NaN when a pivot fails.
+template <int CMAX>
+__device__ __forceinline__ double block_score(const double *w, const double *diag, const float *A, int d,
+                                              int j0, int c)
+{
+    double v[CMAX], M[CMAX][CMAX];
+#pragma unroll
+    for (int i = 0; i < CMAX; ++i) {
+        if (i >= c) continue;
+        v[i] = w[j0 + i];
+#pragma unroll
+        for (int j = 0; j < CMAX; ++j) {
+            if (j > i) continue;
+            M[i][j] = (i == j) ? diag[j0 + i] : (double)A[(size_t)(j0 + i) * d + (j0 + j)];
+        }
+    }
+    double s = 0.0;
+#pragma unroll
+    for (int k = 0; k < CMAX; ++k) {
+        if (k >= c) continue;
+        const double piv = M[k][k];
+        if (!(piv > 0.0)) return __builtin_nan("");
+        const double ip = 1.0 / piv;
+        s += v[k] * v[k] * ip;
+#pragma unroll
+        for (int i = 0; i < CMAX; ++i) {
+            if (i <= k || i >= c) continue;
+            const double f = M[i][k] * ip;
+            v[i] -= f * v[k];
+#pragma unroll
+            for (int j = 0; j < CMAX; ++j) {
+                if (j <= k || j > i) continue;
+                M[i][j] -= f * M[j][k];
+            }
+        }
+    }
+    return s;
+}
+
+template <int MODE, int CMAX>
 __global__ __launch_bounds__(1024) void rows_rank1_kernel(Rank1Args a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -90,7 +138,7 @@ __global__ __launch_bounds__(1024) void rows_rank1_kernel(Rank1Args a)
     const int n_dead = misc[1];
     int m = misc[0];   // live count, tracked in a register by every thread
 
-    int steps = a.k_steps;
+    int steps = a.k_steps;   // block pruning: block steps
     if (MODE == MODE_QUANT) steps = m;
     if (a.stop_counts) {
         int sc = a.stop_counts[row];
@@ -101,6 +149,11 @@ __global__ __launch_bounds__(1024) void rows_rank1_kernel(Rank1Args a)
     const double qmax = (double)a.maxq;
     if (MODE == MODE_QUANT) { qd = (double)a.delta[row]; qo = (double)a.offset[row]; }
     const double iqd = 1.0 / qd;
+
+    const int bc = (MODE == MODE_BLOCK) ? a.blk_c : 1;
+    if (MODE == MODE_BLOCK) steps *= bc;   // from here on in single eliminations
+    int pblock = 0;                        // block being eliminated
+    double block_loss = 0.0;               // its accumulated loss (thread 0)
 
     const bool vec4 = (d % 4 == 0);
     bool failed = false;
@@ -113,6 +166,33 @@ __global__ __launch_bounds__(1024) void rows_rank1_kernel(Rank1Args a)
         if (t < 0) {
             p = dead[t + n_dead];
             app = diag[p];
+        } else if (MODE == MODE_BLOCK) {
+            const int sub = t % bc;
+            if (sub == 0) {
+                // ---- (1) selection over the live blocks
+                Cand c;
+                c.s = __builtin_inff();
+                c.j = 0x7fffffff;
+                for (int b = tid; b < d / bc; b += nthr) {
+                    if (pos[b * bc] == 0xffff) continue;
+                    float s = (float)block_score<CMAX>(w, diag, A, d, b * bc, bc);
+                    if (cand_less(s, b, c.s, c.j)) { c.s = s; c.j = b; }
+                }
+                c = block_argmin(c, red_s, red_j);
+                pblock = c.j;
+                if (pblock == 0x7fffffff) { failed = true; break; }
+                block_loss = 0.0;
+            }
+            p = pblock * bc + sub;
+            app = diag[p];
+            wp = w[p];
+            if (tid == 0) {
+                block_loss += wp * wp / (2.0 * app);
+                if (sub == bc - 1) {
+                    a.order[(size_t)row * a.out_ld + t / bc] = pblock;
+                    a.loss[(size_t)row * a.out_ld + t / bc] = (float)block_loss;
+                }
+            }
         } else {
             // ---- (1) selection: error in fp64, the compared ratio in fp32 (hardware reciprocal)
             Cand c;
@@ -217,8 +297,8 @@ __global__ __launch_bounds__(1024) void rows_rank1_kernel(Rank1Args a)
             m -= 1;
         }
         __syncthreads();
-        if (t >= 0 && a.trace) {
-            float *tr = a.trace + ((size_t)row * a.out_ld + t) * d;
+        if (t >= 0 && a.trace && (t + 1) % bc == 0) {
+            float *tr = a.trace + ((size_t)row * a.out_ld + t / bc) * d;
             for (int j = tid; j < d; j += nthr) tr[j] = (float)w[j];
         }
     }
@@ -259,6 +339,8 @@ int rank1_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, int 
 {
     Rank1Args a;
     a.outliers = (flags & OBC_QUANT_OUTLIERS) ? 1 : 0;
+    a.blk_c = (mode == MODE_BLOCK) ? nm_m : 0;   // block pruning passes its block size as nm_m
+    if (mode == MODE_BLOCK) nm_n = nm_m = 0;
     a.W = W; a.Hinv = Hinv; a.R = R; a.d = d; a.k_steps = k_steps; a.nm_n = nm_n; a.nm_m = nm_m;
     a.stop_counts = stop_counts; a.delta = delta; a.offset = offset; a.maxq = maxq; a.live_in = live;
     a.order = order; a.loss = loss; a.codes = codes; a.W_out = W_out; a.trace = trace;
@@ -281,16 +363,25 @@ int rank1_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, int 
     if (R == 0) return OBC_OK;
     // live-set model of Algorithm 1: step t reads and writes the (d - t)^2 live entries
     double mm = 0.0;
-    for (int t = 0; t < k_steps; ++t) mm += (double)(d - t) * (double)(d - t);
+    const int singles = (mode == MODE_BLOCK) ? k_steps * a.blk_c : k_steps;
+    for (int t = 0; t < singles; ++t) mm += (double)(d - t) * (double)(d - t);
     obc_scope sc(ctx, OBC_KERNEL_RANK1, resident ? 0.0 : (double)R * 8.0 * mm, (double)R * 2.0 * mm);
     if (mode == MODE_PRUNE) {
-        OBC_HIP(ctx, hipFuncSetAttribute((const void *)rows_rank1_kernel<MODE_PRUNE>,
+        OBC_HIP(ctx, hipFuncSetAttribute((const void *)rows_rank1_kernel<MODE_PRUNE, 1>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        rows_rank1_kernel<MODE_PRUNE><<<R, threads, lds, ctx->stream>>>(a);
+        rows_rank1_kernel<MODE_PRUNE, 1><<<R, threads, lds, ctx->stream>>>(a);
+    } else if (mode == MODE_QUANT) {
+        OBC_HIP(ctx, hipFuncSetAttribute((const void *)rows_rank1_kernel<MODE_QUANT, 1>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        rows_rank1_kernel<MODE_QUANT, 1><<<R, threads, lds, ctx->stream>>>(a);
+    } else if (a.blk_c <= 4) {
+        OBC_HIP(ctx, hipFuncSetAttribute((const void *)rows_rank1_kernel<MODE_BLOCK, 4>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        rows_rank1_kernel<MODE_BLOCK, 4><<<R, threads, lds, ctx->stream>>>(a);
     } else {
-        OBC_HIP(ctx, hipFuncSetAttribute((const void *)rows_rank1_kernel<MODE_QUANT>,
+        OBC_HIP(ctx, hipFuncSetAttribute((const void *)rows_rank1_kernel<MODE_BLOCK, 8>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        rows_rank1_kernel<MODE_QUANT><<<R, threads, lds, ctx->stream>>>(a);
+        rows_rank1_kernel<MODE_BLOCK, 8><<<R, threads, lds, ctx->stream>>>(a);
     }
     OBC_LAUNCH_CHECK(ctx, "rows_rank1_kernel");
     return OBC_OK;

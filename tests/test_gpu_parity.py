@@ -227,6 +227,78 @@ def test_strategies_agree_on_order(obc):
     assert torch.allclose(a["loss"], b["loss"], rtol=1e-3, atol=1e-9)
 
 
+# ------------------------------------------------------------------------------ block pruning
+def _check_blocks(obc, orc, W, Hinv, c, k_blocks, strategy, want_trace=False):
+    res = obc.obc_prune_blocks(W, Hinv, c, k_blocks=k_blocks, want_trace=want_trace, strategy=strategy)
+    obc.obc_check()
+    A, Wn = _np(Hinv).astype(np.float64), _np(W).astype(np.float64)
+    order, loss, Wo = _np(res["order"]), _np(res["loss"]), _np(res["W"]).astype(np.float64)
+    swaps = 0
+    for i in range(W.shape[0]):
+        g = order[i, :k_blocks].astype(np.int32)
+        assert len(set(g.tolist())) == k_blocks
+        r = orc.block_prune_row(A, Wn[i], c, k_blocks=k_blocks, want_trace=want_trace)
+        if not np.array_equal(r.order, g):
+            swaps += 1
+            r = orc.block_prune_row(A, Wn[i], c, k_blocks=k_blocks, forced=g, want_trace=want_trace)
+            gap = r.pick_score - r.min_score
+            assert np.all(gap <= 1e-6 * r.min_score + 1e-12 * r.min_score.max()), (i, gap.max())
+        nrm = np.linalg.norm(r.w)
+        assert np.linalg.norm(Wo[i] - r.w) <= 1e-4 * nrm + 1e-30
+        P = np.concatenate([np.arange(b * c, b * c + c) for b in g]) if k_blocks else np.zeros(0, int)
+        assert np.all(Wo[i][P] == 0.0)
+        tot = r.loss.sum()
+        assert abs(loss[i, :k_blocks].astype(np.float64).sum() - tot) <= 1e-3 * tot
+        assert np.allclose(loss[i, :k_blocks], r.loss, rtol=5e-3, atol=1e-6 * r.loss.max())
+        if want_trace:
+            gt = _np(res["trace"])[i].astype(np.float64)
+            num = np.linalg.norm(gt - r.trace, axis=1)
+            assert np.all(num <= 1e-4 * np.linalg.norm(r.trace, axis=1) + 1e-30)
+    return res, swaps
+
+
+@pytest.mark.parametrize("strategy", [1])
+@pytest.mark.parametrize("d,R,c,kb", [(32, 16, 4, 8), (32, 16, 2, 16), (200, 4, 8, 20), (576, 4, 4, 100),
+                                      (260, 3, 4, 65), (126, 3, 3, 42)])
+def test_prune_blocks_matches_oracle(obc, orc, strategy, d, R, c, kb):
+    name = "lin16x32" if d == 32 else "conv64x576"
+    W, X = _layer(name, d_col=d, d_row=R, n_samples=max(256, 3 * d))
+    Hinv = _hinv(obc, X)
+    _check_blocks(obc, orc, W, Hinv, c, kb, strategy, want_trace=(d <= 200))
+
+
+@pytest.mark.parametrize("strategy", [1])
+def test_prune_blocks_of_one_is_prune_rows(obc, strategy):
+    W, X = _layer("conv64x576", d_col=260, d_row=4, n_samples=2000)
+    Hinv = _hinv(obc, X)
+    a = obc.obc_prune_rows(W, Hinv, k_steps=100, strategy=strategy)
+    b = obc.obc_prune_blocks(W, Hinv, 1, k_blocks=100, strategy=strategy)
+    obc.obc_check()
+    assert torch.equal(a["order"], b["order"])
+    assert torch.allclose(a["loss"], b["loss"], rtol=1e-6, atol=0)
+    assert torch.allclose(a["W"], b["W"], rtol=1e-6, atol=1e-9)
+
+
+def test_block_traces_feed_the_global_step(obc, orc):
+    # Alg. 2 on the block loss traces, then the weights of the chosen per-row block counts both by
+    # replay (stop_counts) and from the stored trace
+    W, X = _layer("conv64x576", d_col=128, d_row=12, n_samples=1000)
+    Hinv = _hinv(obc, X)
+    c = 4
+    full = obc.obc_prune_blocks(W, Hinv, c, want_trace=True)
+    k = (12 * 32) // 2
+    counts, block_mask = obc.obc_global_select(full["loss"], full["order"], k)
+    ref = orc.global_select(_np(full["loss"]).astype(np.float64), k)
+    assert np.array_equal(_np(counts), ref)
+    assert int(block_mask.sum()) == k
+    replay = obc.obc_prune_blocks(W, Hinv, c, stop_counts=counts)
+    gathered = obc.obc_gather_trace(W, full["trace"], counts)
+    obc.obc_check()
+    assert torch.equal(replay["W"], gathered)
+    zeros = (gathered == 0).sum(dim=1)
+    assert torch.equal(zeros.to(torch.int32), counts * c)
+
+
 # ------------------------------------------------------------------------------ OBQ rows
 def _check_quant(obc, orc, W, Hinv, bits, strategy, live=None, rows=None, grid=None, outliers=False):
     if grid is None:
