@@ -33,6 +33,11 @@ WORKLOADS = {
     "conv512x4608-prune50": ("conv512x4608", "prune50"),
     "conv512x4608-compound": ("conv512x4608", "compound50"),   # prune to 50 %, then OBQ 4-bit on survivors
     "lin16x32-prune50": ("lin16x32", "prune50"),
+    # widened rows: block pruning (blocks of 4) to 50 % with the global step over the block traces, and
+    # the sequential variant (inputs from a perturbed "compressed" model: re-fit, then OBQ)
+    "conv256x2304-block4-50": ("conv256x2304", "block50"),
+    "ffn768x3072-block4-50": ("ffn768x3072", "block50"),
+    "conv256x2304-seqobq4": ("conv256x2304", "seqobq4"),
 }
 DEFAULT_WORKLOAD = "conv256x2304-obq4"
 HBM_PEAK_GBS = 8000.0
@@ -71,14 +76,18 @@ def main():
     N = X.shape[1]
     ctx = pkg.Context()
 
-    if task.startswith("prune") or task.startswith("compound"):
+    BC = 4
+    if task.startswith("block"):
+        sparsity = int(task[-2:]) / 100.0
+        k_steps, nm = d // BC, (0, 0)      # block steps per row
+    elif task.startswith("prune") or task.startswith("compound"):
         sparsity = int(task[-2:]) / 100.0
         k_steps, nm = d, (0, 0)
     elif task == "nm24":
         k_steps, nm = d // 2, (2, 4)
     else:
         k_steps, nm = d, (0, 0)
-    row_steps = R * k_steps
+    row_steps = R * k_steps * (BC if task.startswith("block") else 1)   # single eliminations
     if task.startswith("compound"):
         row_steps += R * d      # second pass: eliminations of the pruned + OBQ steps of the survivors
 
@@ -87,13 +96,21 @@ def main():
     out = dict(order=torch.empty(R, k_steps, dtype=torch.int32, device="cuda"),
                loss=torch.empty(R, k_steps, device="cuda"),
                W=torch.empty(R, d, device="cuda"))
-    if task.startswith("obq"):
+    if task.endswith("obq4"):
         out["codes"] = torch.empty(R, d, dtype=torch.int32, device="cuda")
+    if task == "seqobq4":
+        # stand-in for the inputs of the already compressed model: the dense inputs, perturbed;
+        # Y = the dense layer's outputs on the dense inputs
+        torch.manual_seed(11)
+        Y = (W @ X).contiguous()
+        X = (X + 0.1 * X.std() * torch.randn_like(X)).contiguous()
+        Cm = torch.empty(R, d, device="cuda")
+        Wfit = torch.empty(R, d, device="cuda")
     qout = None
     if task.startswith("compound"):
         qout = dict(order=torch.empty(R, d, dtype=torch.int32, device="cuda"), loss=torch.empty(R, d, device="cuda"),
                     W=torch.empty(R, d, device="cuda"), codes=torch.empty(R, d, dtype=torch.int32, device="cuda"))
-    want_trace = task.startswith("prune") or task.startswith("compound")
+    want_trace = task.startswith("prune") or task.startswith("compound") or task.startswith("block")
     trace_bytes = R * k_steps * d * 4
     if want_trace and trace_bytes > 120e9:
         want_trace = False        # largest layers: recover by replay instead of the HBM trace
@@ -109,9 +126,18 @@ def main():
         e[0].record()
         ctx.obc_hessian(X, damp_rel=0.01, H=H)
         e[1].record()
-        ctx.obc_invert(H)
+        if task == "seqobq4":
+            ctx.obc_cross(X, Y, C=Cm)
+            ctx.obc_refit(H, Cm, invert_in_place=True, W_out=Wfit)
+        else:
+            ctx.obc_invert(H)
         e[2].record()
-        if task.startswith("obq"):
+        if task == "seqobq4":
+            delta, offset, maxq = ctx.obc_minmax_grid(Wfit, 4)
+            res = ctx.obc_quant_rows(Wfit, H, delta, offset, maxq, strategy=strategy, out=out)
+        elif task.startswith("block"):
+            res = ctx.obc_prune_blocks(W, H, BC, want_trace=want_trace, strategy=strategy)
+        elif task.startswith("obq"):
             delta, offset, maxq = ctx.obc_minmax_grid(W, 4)
             res = ctx.obc_quant_rows(W, H, delta, offset, maxq, strategy=strategy, out=out)
         else:
@@ -119,7 +145,12 @@ def main():
                                      strategy=strategy, out=out)
         e[3].record()
         result = res["W"]
-        if task.startswith("prune") or task.startswith("compound"):
+        if task.startswith("block"):
+            k = obc_inputs.target_count(sparsity, R, d) // BC
+            counts, mask = ctx.obc_global_select(res["loss"], res["order"], k)
+            result = ctx.obc_gather_trace(W, res["trace"], counts)
+            out["order"] = res["order"]
+        elif task.startswith("prune") or task.startswith("compound"):
             k = obc_inputs.target_count(sparsity, R, d)
             counts, mask = ctx.obc_global_select(res["loss"], res["order"], k)
             if want_trace:
@@ -212,20 +243,23 @@ def main():
         n_rows = args.cpu_rows or threads
         n_rows = min(n_rows, R)
         # keep the sample to roughly 10-30 s: the oracle costs ~ k d^2 / 3 inner iterations per row
-        per_row_s = (k_steps * d * d / 3.0) / 0.7e9
+        per_row_s = (k_steps * (BC if task.startswith("block") else 1) * d * d / 3.0) / 0.7e9
         while n_rows > threads and per_row_s * n_rows / threads > 30:
             n_rows //= 2
         A64 = H.cpu().numpy().astype(np.float64)
-        Wn = W[:n_rows].cpu().numpy().astype(np.float64)
+        Wn = (Wfit if task == "seqobq4" else W)[:n_rows].cpu().numpy().astype(np.float64)
         t1 = time.perf_counter()
-        if task.startswith("obq"):
+        if task.startswith("block"):
+            ro = orc.block_prune_rows(A64, Wn, BC, n_threads=threads)
+        elif task.endswith("obq4"):
             grids = [orc.minmax_grid(Wn[i], 4) for i in range(n_rows)]
             ro = orc.quant_rows(A64, Wn, [g[0] for g in grids], [g[1] for g in grids], 15, n_threads=threads)
         else:
             ro = orc.prune_rows(A64, Wn, k_steps=k_steps, nm=nm, n_threads=threads)
         cpu_s = time.perf_counter() - t1
         line["cpu_baseline"] = {
-            "value": n_rows * k_steps / cpu_s, "unit": "row-steps/s", "cores": int(ro["threads"]),
+            "value": n_rows * k_steps * (BC if task.startswith("block") else 1) / cpu_s, "unit": "row-steps/s",
+            "cores": int(ro["threads"]),
             "kind": "oracle", "sample": "%d of %d rows of %s, all %d steps each, %.1f s" % (
                 n_rows, R, args.workload, k_steps, cpu_s),
         }

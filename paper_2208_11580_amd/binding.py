@@ -28,7 +28,7 @@ EXPORTS = [
     "obc_hessian_workspace_bytes", "obc_hessian",
     "obc_invert_workspace_bytes", "obc_invert",
     "obc_cross_workspace_bytes", "obc_cross", "obc_refit_workspace_bytes", "obc_refit",
-    "obc_rows_workspace_bytes", "obc_prune_rows", "obc_prune_blocks", "obc_quant_rows", "obc_minmax_grid",
+    "obc_rows_workspace_bytes", "obc_prune_rows", "obc_blocks_workspace_bytes", "obc_prune_blocks", "obc_quant_rows", "obc_minmax_grid",
     "obc_global_select_workspace_bytes", "obc_global_select", "obc_gather_trace",
 ]
 
@@ -77,6 +77,7 @@ def load_library():
     lib.obc_rows_workspace_bytes.argtypes = [c_int, c_int, c_int, sp]
     lib.obc_prune_rows.argtypes = [vp, vp, vp, c_int, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp,
                                    c_int, vp, c_size_t]
+    lib.obc_blocks_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, sp]
     lib.obc_prune_blocks.argtypes = [vp, vp, vp, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp, c_int, vp, c_size_t]
     lib.obc_quant_rows.argtypes = [vp, vp, vp, c_int, c_int, vp, vp, c_int, vp, c_int, vp, vp, vp, vp, c_int,
                                    vp, c_size_t]
@@ -259,7 +260,11 @@ class Context:
         loss = torch.empty(R, k_blocks, dtype=torch.float32, device=dev)
         W_out = torch.empty(R, d, dtype=torch.float32, device=dev)
         trace = torch.empty(R, k_blocks, d, dtype=torch.float32, device=dev) if want_trace else None
-        ws = self.workspace(self.rows_workspace_bytes(R, d, STRATEGY_RANK1))
+        need = c_size_t()
+        rc = self.lib.obc_blocks_workspace_bytes(R, d, int(c), int(strategy), byref(need))
+        if rc != OBC_OK:
+            raise ObcError(rc, "obc_blocks_workspace_bytes")
+        ws = self.workspace(need.value)
         self._ck(self.lib.obc_prune_blocks(
             self.h, _ptr(W, torch.float32), _ptr(Hinv, torch.float32), R, d, int(c), int(k_blocks),
             _ptr(stop_counts, torch.int32), _ptr(order), _ptr(loss), _ptr(W_out), _ptr(trace),

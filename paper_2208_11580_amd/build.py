@@ -29,19 +29,35 @@ def build_lib(force: bool = False, verbose: bool = False) -> str:
     os.makedirs(OBJDIR, exist_ok=True)
     headers = glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(HERE, "..", "include", "*.h"))
     hdr_time = max(os.path.getmtime(h) for h in headers)
-    objs, procs = [], []
+    objs, todo = [], []
     for src in sources():
         obj = os.path.join(OBJDIR, os.path.basename(src)[:-4] + ".o")
         objs.append(obj)
         stale = force or not os.path.exists(obj) or os.path.getmtime(obj) < max(os.path.getmtime(src), hdr_time)
         if stale:
-            cmd = [HIPCC] + FLAGS + ["-c", src, "-o", obj]
-            if verbose:
-                print(" ".join(cmd), flush=True)
-            procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)))
+            todo.append((src, obj))
+    # at most JOBS compilers at a time, the long ones (the unrolled panel kernels) first
+    jobs = max(1, int(os.environ.get("OBC_BUILD_JOBS", min(8, os.cpu_count() or 1))))
+    todo.sort(key=lambda so: (0 if "panel_" in os.path.basename(so[0]) else 1, so[0]))
+    procs, running = [], []
+    for src, obj in todo:
+        while len(running) >= jobs:
+            running[0].wait()
+            running = [r for r in running if r.poll() is None]
+        cmd = [HIPCC] + FLAGS + ["-c", src, "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        log = open(obj + ".log", "wb")
+        pr = subprocess.Popen(cmd, stdout=log, stderr=subprocess.STDOUT)
+        log.close()
+        procs.append((src, pr, obj + ".log"))
+        running.append(pr)
     failed = False
-    for src, p in procs:
-        out, _ = p.communicate()
+    for src, p, logname in procs:
+        p.wait()
+        with open(logname, "rb") as f:
+            out = f.read()
+        os.remove(logname)
         text = out.decode(errors="replace")
         text = "\n".join(l for l in text.splitlines() if "packed-fp32-ops" not in l)
         if p.returncode != 0:

@@ -31,6 +31,11 @@ struct PanelRegs {
     int og[EPT];
     bool alive[EPT];
     float u[BR][EPT];   // u_r for the first BR steps of the block; later ones live in LDS
+    // block pruning only: row j of the 4 x 4 diagonal block of the current inverse that element j
+    // belongs to (entry k = A[j][4 (j / 4) + k]; the element's own slot is not used), and the first
+    // position of the block being eliminated
+    float ob[EPT][4];
+    int p0;
 };
 
 struct PanelShared {
@@ -40,6 +45,7 @@ struct PanelShared {
     int pivs[BMAX];
     double bc_g, bc_invapp;
     int bc_o, bc_ok;
+    double blk_loss;   // block pruning: loss of the block being eliminated, summed over its weights
 };
 
 // order-preserving map of a float onto unsigned integers
@@ -47,6 +53,56 @@ __device__ __forceinline__ unsigned score_bits(float f)
 {
     unsigned u = __float_as_uint(f);
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// value of lane K of the caller's group of four lanes (DPP quad_perm broadcast); must be called
+// with all four lanes active
+template <int K>
+__device__ __forceinline__ float quad_bcast(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), K * 0x55, 0xf, 0xf, false));
+}
+template <int K>
+__device__ __forceinline__ double quad_bcast(double v)
+{
+    long long b = __double_as_longlong(v);
+    unsigned lo = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)b, K * 0x55, 0xf, 0xf, false);
+    unsigned hi = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)(b >> 32), K * 0x55, 0xf, 0xf, false);
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+
+// Block pruning (Sec. 4 "Block-Sparsity", eq. (5)), blocks of 4: the score w_P^T ((H^-1)_P)^-1 w_P of
+// the block that the calling lane's element belongs to.  The block's four elements sit on four
+// neighbouring lanes (positions 4b .. 4b+3 of the compact index space); every lane gathers the
+// block's weights and its 4 x 4 piece of the inverse and runs the same elimination, so the four
+// lanes get bit-identical scores.  NaN when a pivot is not positive.
+__device__ __forceinline__ double quad_block_score(double w, double dg, const float (&ob)[4])
+{
+    double v[4], M[4][4];
+    v[0] = quad_bcast<0>(w); v[1] = quad_bcast<1>(w); v[2] = quad_bcast<2>(w); v[3] = quad_bcast<3>(w);
+    M[0][0] = quad_bcast<0>(dg); M[1][1] = quad_bcast<1>(dg);
+    M[2][2] = quad_bcast<2>(dg); M[3][3] = quad_bcast<3>(dg);
+    M[1][0] = (double)quad_bcast<1>(ob[0]);
+    M[2][0] = (double)quad_bcast<2>(ob[0]); M[2][1] = (double)quad_bcast<2>(ob[1]);
+    M[3][0] = (double)quad_bcast<3>(ob[0]); M[3][1] = (double)quad_bcast<3>(ob[1]);
+    M[3][2] = (double)quad_bcast<3>(ob[2]);
+    double s = 0.0;
+    bool bad = false;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const double piv = M[k][k];
+        bad = bad || !(piv > 0.0);
+        const double ip = 1.0 / piv;
+        s += v[k] * v[k] * ip;
+#pragma unroll
+        for (int i = k + 1; i < 4; ++i) {
+            const double f = M[i][k] * ip;
+            v[i] -= f * v[k];
+#pragma unroll
+            for (int j = k + 1; j <= i; ++j) M[i][j] -= f * M[j][k];
+        }
+    }
+    return bad ? __builtin_nan("") : s;
 }
 
 // one DPP stage of a 64-bit unsigned minimum: combine with the lane `row_shr` positions down the
@@ -123,6 +179,19 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
     // A candidate is the 64-bit key (order-preserving bits of the score, index): the unsigned
     // minimum of the keys is the argmin with ties to the lowest index.
     unsigned long long key = ~0ull;
+    if constexpr (MODE == MODE_BLOCK) {
+        // a block is chosen every fourth step; the three steps after it take its other weights
+        if constexpr (S % 4 == 0) {
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) {
+                const float sc = (float)quad_block_score(st.w[e], st.dg[e], st.ob[e]);
+                if (st.alive[e] && sc == sc) {
+                    unsigned long long k = ((unsigned long long)score_bits(sc) << 32) | (unsigned)((tid & ~3) + e * T);
+                    key = k < key ? k : key;
+                }
+            }
+        }
+    } else {
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
         if (!st.alive[e]) continue;
@@ -148,14 +217,22 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
             key = k < key ? k : key;
         }
     }
-    key = wave_min_key(key);
-    if (lane == 0) sh.red_k[S & 1][wave] = key;
-    OBC_TICK(1);   // selection + wave reduction
-    __syncthreads();
-    OBC_TICK(2);   // barrier 1
-    key = row16_min_key((lane & 15) < NW ? sh.red_k[S & 1][lane & 15] : ~0ull);
-    if (key == ~0ull) return 2;
-    const int p = (int)(unsigned)key;
+    }
+    int p;
+    if constexpr (MODE == MODE_BLOCK && S % 4 != 0) {
+        __syncthreads();   // the previous step's readers of the shared step data are done
+        p = st.p0 + S % 4;
+    } else {
+        key = wave_min_key(key);
+        if (lane == 0) sh.red_k[S & 1][wave] = key;
+        OBC_TICK(1);   // selection + wave reduction
+        __syncthreads();
+        OBC_TICK(2);   // barrier 1
+        key = row16_min_key((lane & 15) < NW ? sh.red_k[S & 1][lane & 15] : ~0ull);
+        if (key == ~0ull) return 2;
+        p = (int)(unsigned)key;
+        if constexpr (MODE == MODE_BLOCK) st.p0 = p;
+    }
 
     // ---- (2) fetch the owned part of row p of A0.  Only the lower triangle of A0 is kept up to
     // date (the matrix is symmetric): entry (p, j) is read as (max(p, j), min(p, j)), i.e. along
@@ -206,7 +283,21 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
             sh.cvec[r] = __fmul_rn(ur, sh.invd_s[r]);
         }
         if (a.nm_m > 0 && op >= 0) blk[op / a.nm_m] += 1;
-        if (ok && op >= 0) {
+        if (MODE == MODE_BLOCK) {
+            // the block's loss is the sum of its four single losses (owners of consecutive steps
+            // are separated by the step's barriers)
+            const double l = wp * wp / (2.0 * ap);
+            const double acc = (S % 4 == 0) ? l : sh.blk_loss + l;
+            sh.blk_loss = acc;
+            if (ok) {
+                a.W_out[(size_t)pr.row * pr.d + op] = 0.f;
+                if (S % 4 == 3) {
+                    const int t = (pr.done + S) / 4;
+                    a.order[(size_t)pr.row * a.out_ld + t] = op / 4;
+                    a.loss[(size_t)pr.row * a.out_ld + t] = (float)acc;
+                }
+            }
+        } else if (ok && op >= 0) {
             const int t = pr.done + S - pr.ndead;
             const double er = target - wp;
             a.order[(size_t)pr.row * a.out_ld + t] = op;
@@ -244,6 +335,14 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
         }
         if constexpr (S < BR) st.u[S < BR ? S : 0][e] = c;
         else ul[(S - BR) * CAP + j] = c;
+        if constexpr (MODE == MODE_BLOCK) {
+            // Lemma 1 on the element's row of its own 4 x 4 block: A[j][j'] -= u[j] u[j'] / a
+            const float cs = c * (float)invapp;
+            st.ob[e][0] = fmaf(-cs, quad_bcast<0>(c), st.ob[e][0]);
+            st.ob[e][1] = fmaf(-cs, quad_bcast<1>(c), st.ob[e][1]);
+            st.ob[e][2] = fmaf(-cs, quad_bcast<2>(c), st.ob[e][2]);
+            st.ob[e][3] = fmaf(-cs, quad_bcast<3>(c), st.ob[e][3]);
+        }
         if (st.alive[e]) {
             if (j == p) {
                 st.alive[e] = false;
@@ -255,6 +354,12 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
         }
     }
     OBC_TICK(5);   // wait for the row, correction, w / diag update
+    if (MODE == MODE_BLOCK && a.trace && S % 4 == 3) {
+        float *tr = a.trace + ((size_t)pr.row * a.out_ld + (pr.done + S) / 4) * pr.d;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e)
+            if (st.alive[e]) tr[st.og[e]] = (float)st.w[e];
+    }
     if (MODE == MODE_PRUNE && a.trace && !isdead) {
         float *tr = a.trace + ((size_t)pr.row * a.out_ld + (pr.done + S - pr.ndead)) * pr.d;
 #pragma unroll
@@ -321,6 +426,21 @@ __global__ __launch_bounds__(T) void panel_kernel(PanelArgs a)
         st.w[e] = st.alive[e] ? gw[j] : 0.0;
         st.dg[e] = st.alive[e] ? gd[j] : 1.0;
         st.og[e] = st.alive[e] ? go[j] : 0;
+    }
+    if constexpr (MODE == MODE_BLOCK) {
+        // the element's row of its 4 x 4 diagonal block, from the lower triangle of the matrix
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const int j = tid + e * T, j0 = j & ~3;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int jj = j0 + k;
+                const int hi = (jj <= j) ? j : jj, lo = (jj <= j) ? jj : j;
+                const size_t off = pr.swz ? quad_index(hi, lo, pr.ld) : (size_t)hi * pr.ld + lo;
+                st.ob[e][k] = (j < m) ? pr.Acur[off] : 0.f;
+            }
+        }
+        st.p0 = 0;
     }
     const int nmb = a.nm_m > 0 ? d / a.nm_m : 0;
     for (int b = tid; b < nmb; b += T) blk[b] = a.ws.blk[(size_t)row * d + b];
@@ -392,6 +512,23 @@ __global__ __launch_bounds__(T) void panel_kernel(PanelArgs a)
         }                                                                                           \
         if (mode == MODE_PRUNE) hipLaunchKernelGGL(kp, dim3(R), dim3(T), lds, st, a);               \
         else hipLaunchKernelGGL(kq, dim3(R), dim3(T), lds, st, a);                                  \
+        return 0;                                                                                   \
+    }
+
+// The block-pruning instance of a variant, in a translation unit of its own.
+#define OBC_DEFINE_PANEL_BLOCK(T, EPT, BR, BL)                                                      \
+    int launch_panel_block_##T##_##EPT##_##BR##_##BL(int, int R, size_t lds_nm, hipStream_t st,     \
+                                                     const PanelArgs &a)                            \
+    {                                                                                               \
+        const size_t lds = (size_t)(BL) * (T) * (EPT) * sizeof(float) + lds_nm;                     \
+        auto kb = panel_kernel<MODE_BLOCK, T, EPT, BR, BL>;                                         \
+        static bool attr_set = false;                                                               \
+        if (!attr_set && lds > 48 * 1024) {                                                         \
+            if (hipFuncSetAttribute((const void *)kb, hipFuncAttributeMaxDynamicSharedMemorySize,   \
+                                    (int)(160 * 1024 - 2048)) != hipSuccess) return -1;             \
+            attr_set = true;                                                                        \
+        }                                                                                           \
+        hipLaunchKernelGGL(kb, dim3(R), dim3(T), lds, st, a);                                       \
         return 0;                                                                                   \
     }
 

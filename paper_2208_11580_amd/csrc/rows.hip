@@ -28,6 +28,14 @@ int pick_strategy(int strategy, int d)
     return d <= blocked_max_d() ? OBC_STRATEGY_BLOCKED : OBC_STRATEGY_RANK1;
 }
 
+// Block pruning: the deferred-update solver handles blocks of 4; -1 when it is asked for others.
+int pick_block_strategy(int strategy, int d, int c)
+{
+    if (strategy == OBC_STRATEGY_BLOCKED) return (c == 4 && d <= blocked_max_d()) ? OBC_STRATEGY_BLOCKED : -1;
+    if (strategy == OBC_STRATEGY_RANK1 || c != 4) return OBC_STRATEGY_RANK1;
+    return pick_strategy(OBC_STRATEGY_AUTO, d);
+}
+
 // The row's grid over its live weights (min-max, or symmetric about zero); one wave per row.
 __global__ __launch_bounds__(256) void minmax_grid_kernel(const float *__restrict__ W,
                                                           const uint8_t *__restrict__ live, int R,
@@ -136,11 +144,25 @@ int obc_prune_blocks(obc_ctx *ctx, const float *W, const float *Hinv, int R, int
         return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_prune_blocks: null W, Hinv, order, loss or W_out");
     if (strategy < OBC_STRATEGY_AUTO || strategy > OBC_STRATEGY_BLOCKED)
         return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_prune_blocks: unknown strategy %d", strategy);
-    if (strategy == OBC_STRATEGY_BLOCKED)
-        return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_prune_blocks: the deferred-update solver does not do block pruning");
+    const int s = pick_block_strategy(strategy, d, c);
+    if (s < 0)
+        return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_prune_blocks: the deferred-update solver handles blocks of 4 only");
     if (R == 0) return OBC_OK;
-    return rank1_launch(ctx, MODE_BLOCK, W, Hinv, R, d, k_blocks, 0, c, stop_counts, nullptr, nullptr, 0,
-                        nullptr, 0, order, loss, nullptr, W_out, trace, k_blocks, ws, ws_bytes);
+    if (s == OBC_STRATEGY_RANK1)
+        return rank1_launch(ctx, MODE_BLOCK, W, Hinv, R, d, k_blocks, 0, c, stop_counts, nullptr, nullptr, 0,
+                            nullptr, 0, order, loss, nullptr, W_out, trace, k_blocks, ws, ws_bytes);
+    return blocked_launch(ctx, MODE_BLOCK, W, Hinv, R, d, k_blocks * 4, 0, 0, stop_counts, nullptr, nullptr, 0,
+                          nullptr, 0, order, loss, nullptr, W_out, trace, k_blocks, ws, ws_bytes);
+}
+
+int obc_blocks_workspace_bytes(int R, int d, int c, int strategy, size_t *bytes)
+{
+    if (!bytes || R < 0 || d <= 0 || c < 1 || c > 8) return OBC_ERR_BAD_ARG;
+    if (strategy < OBC_STRATEGY_AUTO || strategy > OBC_STRATEGY_BLOCKED) return OBC_ERR_BAD_ARG;
+    const int s = pick_block_strategy(strategy, d, c);
+    if (s < 0) return OBC_ERR_BAD_ARG;
+    *bytes = (s == OBC_STRATEGY_RANK1) ? rank1_workspace_bytes(R, d) : blocked_workspace_bytes(R, d);
+    return OBC_OK;
 }
 
 int obc_quant_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d,

@@ -63,10 +63,12 @@ struct PanelArgs {
     int *status;
 };
 
-// launchers defined in panel_<T>x<EPT>x<BR>x<BL>.hip: T threads, EPT owned indices per thread,
+// launchers defined in panel_<T>x<EPT>x<BR>x<BL>.hip (pruning and OBQ) and
+// panel_block_<T>x<EPT>x<BR>x<BL>.hip (block pruning, blocks of 4): T threads, EPT owned indices per thread,
 // blocks of BR + BL steps (BR vectors in registers, BL in LDS).  Return 0 or -1 (HIP error).
 #define OBC_DECLARE_PANEL(T, EPT, BR, BL) \
-    int launch_panel_##T##_##EPT##_##BR##_##BL(int mode, int R, size_t lds_nm, hipStream_t st, const PanelArgs &a)
+    int launch_panel_##T##_##EPT##_##BR##_##BL(int mode, int R, size_t lds_nm, hipStream_t st, const PanelArgs &a); \
+    int launch_panel_block_##T##_##EPT##_##BR##_##BL(int mode, int R, size_t lds_nm, hipStream_t st, const PanelArgs &a)
 OBC_DECLARE_PANEL(256, 1, 64, 0);
 OBC_DECLARE_PANEL(256, 3, 32, 16);
 OBC_DECLARE_PANEL(1024, 1, 64, 0);

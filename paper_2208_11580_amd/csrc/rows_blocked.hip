@@ -97,11 +97,12 @@ __global__ __launch_bounds__(256) void blocked_init_kernel(InitArgs a)
     atomicAdd(&cnt, dead_local);
     __syncthreads();
     if (tid == 0) {
-        int total = a.k_steps;
+        int total = a.k_steps;   // in single eliminations (block pruning: 4 per block step)
         if (a.mode == MODE_QUANT) total = d;   // eliminations of the dead + one step per survivor
         if (a.stop_counts) {
             int sc = a.stop_counts[row];
             sc = sc < 0 ? 0 : sc;
+            if (a.mode == MODE_BLOCK) sc = sc > d / 4 ? d : sc * 4;
             total = sc < total ? sc : total;
         }
         a.ws.m[row] = d;
@@ -296,9 +297,12 @@ struct Variant {
     int cap;   // largest live size it handles (T * EPT)
     int B;     // steps per block
     int (*launch)(int, int, size_t, hipStream_t, const PanelArgs &);
+    int (*launch_block)(int, int, size_t, hipStream_t, const PanelArgs &);   // block pruning
 };
 
-#define OBC_VARIANT(T, EPT, BR, BL) { (T) * (EPT), (BR) + (BL), launch_panel_##T##_##EPT##_##BR##_##BL }
+#define OBC_VARIANT(T, EPT, BR, BL)                                           \
+    { (T) * (EPT), (BR) + (BL), launch_panel_##T##_##EPT##_##BR##_##BL,       \
+      launch_panel_block_##T##_##EPT##_##BR##_##BL }
 
 const Variant kVariants[] = {
     OBC_VARIANT(256, 1, 64, 0),   OBC_VARIANT(1024, 1, 64, 0), OBC_VARIANT(512, 4, 40, 16),
@@ -379,7 +383,7 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
             const int steps = (host_total - host_done < v->B) ? host_total - host_done : v->B;
             obc_scope sc(ctx, OBC_KERNEL_PANEL, (double)R * steps * 4.0 * m_max,
                          (double)R * steps * (double)steps * m_max);
-            if (v->launch(mode, R, lds_nm, st, pa) != 0)
+            if ((mode == MODE_BLOCK ? v->launch_block : v->launch)(mode, R, lds_nm, st, pa) != 0)
                 return obc_fail(ctx, OBC_ERR_HIP, "panel kernel: cannot set its dynamic LDS size");
         }
         OBC_LAUNCH_CHECK(ctx, "panel_kernel");

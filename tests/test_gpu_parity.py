@@ -257,14 +257,30 @@ def _check_blocks(obc, orc, W, Hinv, c, k_blocks, strategy, want_trace=False):
     return res, swaps
 
 
-@pytest.mark.parametrize("strategy", [1])
-@pytest.mark.parametrize("d,R,c,kb", [(32, 16, 4, 8), (32, 16, 2, 16), (200, 4, 8, 20), (576, 4, 4, 100),
-                                      (260, 3, 4, 65), (126, 3, 3, 42)])
+@pytest.mark.parametrize("strategy,d,R,c,kb", [
+    (1, 32, 16, 4, 8), (1, 32, 16, 2, 16), (1, 200, 4, 8, 20), (1, 576, 4, 4, 100), (1, 260, 3, 4, 65),
+    (1, 126, 3, 3, 42),
+    (2, 32, 16, 4, 8), (2, 200, 4, 4, 50), (2, 576, 4, 4, 100), (2, 260, 3, 4, 65), (2, 576, 3, 4, 144),
+    (2, 768, 2, 4, 192)])
 def test_prune_blocks_matches_oracle(obc, orc, strategy, d, R, c, kb):
-    name = "lin16x32" if d == 32 else "conv64x576"
+    name = "lin16x32" if d == 32 else ("attn768x768" if d == 768 else "conv64x576")
     W, X = _layer(name, d_col=d, d_row=R, n_samples=max(256, 3 * d))
     Hinv = _hinv(obc, X)
     _check_blocks(obc, orc, W, Hinv, c, kb, strategy, want_trace=(d <= 200))
+
+
+def test_block_strategies_agree(obc):
+    W, X = _layer("conv64x576", d_col=576, d_row=8, n_samples=3000)
+    Hinv = _hinv(obc, X)
+    a = obc.obc_prune_blocks(W, Hinv, 4, strategy=1)
+    b = obc.obc_prune_blocks(W, Hinv, 4, strategy=2)
+    obc.obc_check()
+    same = (a["order"] == b["order"]).float().mean().item()
+    assert same > 0.98, same
+    assert torch.allclose(a["loss"].sum(dim=1), b["loss"].sum(dim=1), rtol=1e-4)
+    import paper_2208_11580_amd as pkg
+    with pytest.raises(pkg.ObcError):
+        obc.obc_prune_blocks(W, Hinv, 2, strategy=2)     # the deferred-update solver does blocks of 4
 
 
 @pytest.mark.parametrize("strategy", [1])
@@ -279,14 +295,15 @@ def test_prune_blocks_of_one_is_prune_rows(obc, strategy):
     assert torch.allclose(a["W"], b["W"], rtol=1e-6, atol=1e-9)
 
 
-def test_block_traces_feed_the_global_step(obc, orc):
+@pytest.mark.parametrize("d", [128, 320])
+def test_block_traces_feed_the_global_step(obc, orc, d):
     # Alg. 2 on the block loss traces, then the weights of the chosen per-row block counts both by
-    # replay (stop_counts) and from the stored trace
-    W, X = _layer("conv64x576", d_col=128, d_row=12, n_samples=1000)
+    # replay (stop_counts) and from the stored trace (d = 128: LDS-resident solver, 320: deferred)
+    W, X = _layer("conv64x576", d_col=d, d_row=12, n_samples=1000)
     Hinv = _hinv(obc, X)
     c = 4
     full = obc.obc_prune_blocks(W, Hinv, c, want_trace=True)
-    k = (12 * 32) // 2
+    k = (12 * (d // 4)) // 2
     counts, block_mask = obc.obc_global_select(full["loss"], full["order"], k)
     ref = orc.global_select(_np(full["loss"]).astype(np.float64), k)
     assert np.array_equal(_np(counts), ref)
