@@ -130,3 +130,35 @@ def check_row(orc, stats, mode, Hinv32, w32, g_order, g_loss, g_w, k_steps, nm=(
         ok = num <= W_RTOL * den + 1e-30
         assert np.all(ok), "trace differs at steps %s" % np.flatnonzero(~ok)[:5]
     return r
+
+
+def check_block_row(orc, Hinv32, w32, c, g_order, g_loss, g_w, k_blocks, g_trace=None):
+    """Block pruning (blocks of c): compare one GPU row with the oracle, same protocol as check_row
+    with blocks as the unit.  Returns True when the oracle had to follow a near-tie swap."""
+    A = np.asarray(Hinv32, np.float64)
+    w = np.asarray(w32, np.float64)
+    g = np.asarray(g_order[:k_blocks], np.int32)
+    assert len(set(g.tolist())) == k_blocks, "GPU order repeats a block"
+    want_trace = g_trace is not None
+    r = orc.block_prune_row(A, w, c, k_blocks=k_blocks, want_trace=want_trace)
+    swapped = not np.array_equal(r.order, g)
+    if swapped:
+        r = orc.block_prune_row(A, w, c, k_blocks=k_blocks, forced=g, want_trace=want_trace)
+        gap = r.pick_score - r.min_score
+        bad = gap > ORDER_GAP * r.min_score + 1e-12 * r.min_score.max()
+        assert not np.any(bad), "GPU block beyond the 1e-6 gap at steps %s" % np.flatnonzero(bad)[:5]
+    gw = np.asarray(g_w, np.float64)
+    nrm = np.linalg.norm(r.w)
+    assert np.linalg.norm(gw - r.w) <= W_RTOL * nrm + 1e-30
+    if k_blocks:
+        P = np.concatenate([np.arange(b * c, b * c + c) for b in g])
+        assert np.all(gw[P] == 0.0), "pruned blocks must be exactly zero"
+        gl = np.asarray(g_loss[:k_blocks], np.float64)
+        tot = r.loss.sum()
+        assert abs(gl.sum() - tot) <= LOSS_RTOL * tot
+        assert np.allclose(gl, r.loss, rtol=5e-3, atol=1e-6 * r.loss.max())
+    if want_trace:
+        gt = np.asarray(g_trace[:k_blocks], np.float64)
+        num = np.linalg.norm(gt - r.trace, axis=1)
+        assert np.all(num <= W_RTOL * np.linalg.norm(r.trace, axis=1) + 1e-30)
+    return swapped

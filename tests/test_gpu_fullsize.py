@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import obc_inputs
-from tests.parity import RowParity, check_row
+from tests.parity import RowParity, check_block_row, check_row
 
 pytestmark = pytest.mark.gpu
 
@@ -182,3 +182,69 @@ def test_rank1_strategy_at_full_width(obc, orc):
     qb = obc.obc_quant_rows(W, Hinv, delta, offset, maxq, strategy=pkg.STRATEGY_BLOCKED)
     assert (q["order"] != qb["order"]).float().mean().item() < 0.002
     assert (q["codes"] != qb["codes"]).float().mean().item() < 0.002
+
+
+def test_conv256x2304_block4_sampled_rows(obc, orc):
+    """Block pruning (blocks of 4) of the whole 256 x 2304 layer in the deferred-update solver; the
+    oracle replays sampled rows, the rest is checked through properties."""
+    W, X, _ = obc_inputs.make_layer("conv256x2304", device="cuda")
+    R, d = W.shape
+    c = 4
+    H = obc.obc_hessian(X)
+    Hd = torch.tensor(_np(H).astype(np.float64), device="cuda")
+    Hinv = obc.obc_invert(H)
+    kb = d // c // 2                     # half of the blocks of every row
+    res = obc.obc_prune_blocks(W, Hinv, c, k_blocks=kb)
+    obc.obc_check()
+    A = _np(Hinv)
+    rows = [3, 130]
+    swaps = 0
+    for i in rows:
+        swaps += check_block_row(orc, A, _np(W[i]), c, _np(res["order"][i]), _np(res["loss"][i]),
+                                 _np(res["W"][i]), kb)
+    print("rows with near-tie swaps:", swaps)
+    # every row: zeros exactly on the chosen aligned blocks, nowhere else
+    zero = (res["W"] == 0)
+    blk_zero = zero.view(R, d // c, c)
+    assert torch.all(blk_zero.all(dim=2) == blk_zero.any(dim=2))
+    chosen = torch.zeros(R, d // c, dtype=torch.bool, device="cuda")
+    chosen.scatter_(1, res["order"].long(), True)
+    assert torch.equal(chosen, blk_zero.all(dim=2))
+    assert torch.all(res["loss"] >= 0)
+    # loss identity on every row: the block losses add up to 1/2 (w - w^)^T H (w - w^)
+    dW = (W - res["W"]).double()
+    q = 0.5 * ((dW @ Hd) * dW).sum(dim=1)
+    assert torch.allclose(res["loss"].double().sum(dim=1), q, rtol=2e-3)
+
+
+def test_conv256x2304_sequential_obq_with_outlier_heuristic(obc, orc):
+    """The sequential variant at full size: inputs of a perturbed model, re-fit sharing the
+    factorisation with the inverse, then 3-bit OBQ on a symmetric grid shrunk by 20 % with the
+    outlier heuristic; sampled rows against the oracle."""
+    W, X, _ = obc_inputs.make_layer("conv256x2304", device="cuda")
+    R, d = W.shape
+    torch.manual_seed(8)
+    Y = (W @ X).contiguous()
+    Xc = (X + 0.1 * X.std() * torch.randn_like(X)).contiguous()
+    del X
+    H = obc.obc_hessian(Xc)
+    C = obc.obc_cross(Xc, Y)
+    H0 = H.clone()
+    Wr = obc.obc_refit(H, C, invert_in_place=True)
+    # the re-fit against the oracle, fed the GPU's H and C (sampled rows; the solve is per row)
+    rows = [5, 250]
+    ref = orc.refit(_np(H0).astype(np.float64), _np(C[rows]).astype(np.float64))
+    assert np.linalg.norm(_np(Wr[rows]) - ref) <= 1e-6 * np.linalg.norm(ref)
+    delta, offset, maxq = obc.obc_minmax_grid(Wr, 3, symmetric=True)
+    delta = (delta * 0.8).contiguous()
+    offset = (offset * 0.8).contiguous()
+    res = obc.obc_quant_rows(Wr, H, delta, offset, maxq, outliers=True)
+    plain = obc.obc_quant_rows(Wr, H, delta, offset, maxq)
+    obc.obc_check()
+    assert not torch.equal(res["order"], plain["order"])      # the heuristic is active
+    A = _np(H)
+    st = RowParity()
+    for i in rows:
+        check_row(orc, st, "quant", A, _np(Wr[i]), _np(res["order"][i]), _np(res["loss"][i]), _np(res["W"][i]), d,
+                  grid=(float(delta[i]), float(offset[i]), maxq), g_codes=_np(res["codes"][i]), outlier=True)
+    print(st)

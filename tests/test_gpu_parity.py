@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import obc_inputs
-from tests.parity import RowParity, check_row
+from tests.parity import RowParity, check_block_row, check_row
 
 pytestmark = pytest.mark.gpu
 
@@ -231,29 +231,12 @@ def test_strategies_agree_on_order(obc):
 def _check_blocks(obc, orc, W, Hinv, c, k_blocks, strategy, want_trace=False):
     res = obc.obc_prune_blocks(W, Hinv, c, k_blocks=k_blocks, want_trace=want_trace, strategy=strategy)
     obc.obc_check()
-    A, Wn = _np(Hinv).astype(np.float64), _np(W).astype(np.float64)
-    order, loss, Wo = _np(res["order"]), _np(res["loss"]), _np(res["W"]).astype(np.float64)
+    A, Wn = _np(Hinv), _np(W)
+    order, loss, Wo = _np(res["order"]), _np(res["loss"]), _np(res["W"])
     swaps = 0
     for i in range(W.shape[0]):
-        g = order[i, :k_blocks].astype(np.int32)
-        assert len(set(g.tolist())) == k_blocks
-        r = orc.block_prune_row(A, Wn[i], c, k_blocks=k_blocks, want_trace=want_trace)
-        if not np.array_equal(r.order, g):
-            swaps += 1
-            r = orc.block_prune_row(A, Wn[i], c, k_blocks=k_blocks, forced=g, want_trace=want_trace)
-            gap = r.pick_score - r.min_score
-            assert np.all(gap <= 1e-6 * r.min_score + 1e-12 * r.min_score.max()), (i, gap.max())
-        nrm = np.linalg.norm(r.w)
-        assert np.linalg.norm(Wo[i] - r.w) <= 1e-4 * nrm + 1e-30
-        P = np.concatenate([np.arange(b * c, b * c + c) for b in g]) if k_blocks else np.zeros(0, int)
-        assert np.all(Wo[i][P] == 0.0)
-        tot = r.loss.sum()
-        assert abs(loss[i, :k_blocks].astype(np.float64).sum() - tot) <= 1e-3 * tot
-        assert np.allclose(loss[i, :k_blocks], r.loss, rtol=5e-3, atol=1e-6 * r.loss.max())
-        if want_trace:
-            gt = _np(res["trace"])[i].astype(np.float64)
-            num = np.linalg.norm(gt - r.trace, axis=1)
-            assert np.all(num <= 1e-4 * np.linalg.norm(r.trace, axis=1) + 1e-30)
+        swaps += check_block_row(orc, A, Wn[i], c, order[i], loss[i], Wo[i], k_blocks,
+                                 g_trace=_np(res["trace"])[i] if want_trace else None)
     return res, swaps
 
 
