@@ -146,14 +146,17 @@ constexpr unsigned kBufWord3 = 0x00020000u;   // raw buffer, 32-bit data format
 constexpr int kFar = 0x40000000;              // byte offset beyond any matrix: "out of range"
 
 // K is the block size: every row that still has steps to do has exactly K deferred eliminations
-// (a row with fewer has finished and is skipped).
-template <int KMAX>
+// (a row with fewer has finished and is skipped).  A strip is HALVES x 128 rows tall: the U tile
+// of a column block, once in LDS, serves all the strip's halves (loading it is the expensive part
+// of a tile next to the matrix traffic itself), and the F tile covers the whole strip.
+template <int KMAX, int HALVES>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) void flush_kernel(FlushArgs a)
 {
-    __shared__ float Fs[KMAX][FLD];
+    constexpr int SR = HALVES * FT;          // rows per strip
+    __shared__ float Fs[KMAX][SR + 4];
     __shared__ float Us[KMAX][FLD];
-    __shared__ int rowoff_s[FT];   // byte offset of each strip row in the old matrix
-    __shared__ int rowold_s[FT];   // its old compact index
+    __shared__ int rowoff_s[SR];   // byte offset of each strip row in the old matrix
+    __shared__ int rowold_s[SR];   // its old compact index
 
     // workgroups are dealt round-robin to the 8 XCDs: keep all strips of one row on one XCD so
     // that its U panel and index map stay in that XCD's L2
@@ -164,7 +167,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     if (a.ws.nb[row] != KMAX || a.ws.done[row] >= a.ws.total[row]) return;
     constexpr int nb = KMAX;
     const int mn = a.ws.m[row];             // live size after the block (new compact space)
-    const int i0 = strip * FT;
+    const int i0 = strip * SR;
     if (i0 >= mn) return;
 
     const int d = a.d;
@@ -186,17 +189,17 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     const int lrow = 4 * (lane >> 5);        // the lane-dependent part of the accumulator row
 
     // F tile: F[k][i] = -u_k[i] / a_k for the strip's rows; byte offsets of the strip's old rows
-    for (int idx = tid; idx < nbp * FT; idx += 512) {
-        int k = idx / FT, i = idx % FT;
+    for (int idx = tid; idx < nbp * SR; idx += 512) {
+        int k = idx / SR, i = idx % SR;
         int ii = i0 + i;
         float v = 0.f;
         if (k < nb && ii < mn) v = -__fmul_rn(U[(size_t)k * d + ii], invd[k]);
         Fs[k][i] = v;
     }
-    if (tid < FT) {
-        int o = (i0 + tid < mn) ? map[i0 + tid] : -1;
-        rowold_s[tid] = o;
-        rowoff_s[tid] = (o < 0) ? kFar : swz ? ((o >> 2) * ldo * 4 + (o & 3)) * 4 : o * ldo * 4;
+    for (int i = tid; i < SR; i += 512) {
+        int o = (i0 + i < mn) ? map[i0 + i] : -1;
+        rowold_s[i] = o;
+        rowoff_s[i] = (o < 0) ? kFar : swz ? ((o >> 2) * ldo * 4 + (o & 3)) * 4 : o * ldo * 4;
     }
 
     // U tile staging: KMAX x 128 floats by 512 threads
@@ -218,52 +221,76 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         }
     };
     floatx16 acc[2], nxt[2];
-    // strictly-lower tiles: element (i, j) sits at old[map i][map j]
-    auto fetch_c = [&](floatx16(&c)[2], int jold) {
+    // strictly-lower tiles: element (i, j) sits at old[map i][map j]; rb = first strip row of the tile
+    auto fetch_c = [&](floatx16(&c)[2], int jold, int rb) {
         const int joldB = (jold < 0) ? kFar : swz ? jold * 16 : jold * 4;
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                int ro = rowoff_s[wm * 64 + mt * 32 + 8 * (v >> 2) + lrow + (v & 3)];
+                int ro = rowoff_s[rb + wm * 64 + mt * 32 + 8 * (v >> 2) + lrow + (v & 3)];
                 c[mt][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rold, ro + joldB, 0, 0));
             }
     };
     // the diagonal tile: only entries on or below the diagonal exist
-    auto fetch_c_diag = [&](floatx16(&c)[2], int jold) {
+    auto fetch_c_diag = [&](floatx16(&c)[2], int jold, int rb) {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                int oi = rowold_s[wm * 64 + mt * 32 + 8 * (v >> 2) + lrow + (v & 3)];
+                int oi = rowold_s[rb + wm * 64 + mt * 32 + 8 * (v >> 2) + lrow + (v & 3)];
                 int off = (jold < 0 || jold > oi) ? kFar
                           : swz ? (((oi >> 2) * ldo + jold) * 4 + (oi & 3)) * 4 : (oi * ldo + jold) * 4;
                 c[mt][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rold, off, 0, 0));
             }
     };
     auto old_col = [&](int j) { return (j < mn) ? map[j] : -1; };
+    // halves of the strip that hold rows at all
+    const int nh = (mn - i0 + FT - 1) / FT < HALVES ? (mn - i0 + FT - 1) / FT : HALVES;
 
+    // The strip's tiles in the order they are visited: column block j0 = 0, 128, ...; within a
+    // column block the halves hf whose rows reach down to it (rows i0 + 128 hf .. >= j0).
+    // (j0, hf) -> the next one; returns false after the last.
+    auto advance = [&](int &j0, int &hf) {
+        if (hf + 1 < nh) { hf += 1; return true; }
+        j0 += FT;
+        if (j0 >= mn) return false;
+        // first half whose diagonal block is at or beyond column block j0
+        int h0 = (j0 - i0) / FT;
+        if (j0 <= i0) h0 = 0;
+        if (h0 >= nh) return false;
+        hf = h0;
+        return true;
+    };
+    auto fetch_tile = [&](floatx16(&c)[2], int jold, int j0, int hf) {
+        if (j0 == i0 + hf * FT) fetch_c_diag(c, jold, hf * FT);
+        else fetch_c(c, jold, hf * FT);
+    };
+
+    int j0 = 0, hf = 0;
     int jold = old_col(jl);
-    int jold_n = old_col(FT + jl);
     fetch_u(0);
     __syncthreads();                           // rowoff_s / rowold_s visible
-    if (i0 == 0) fetch_c_diag(acc, jold);
-    else fetch_c(acc, jold);
+    fetch_tile(acc, jold, j0, hf);
     stash_u();
-    for (int j0 = 0; j0 <= i0; j0 += FT) {
-        __syncthreads();                       // Us (and, first time, Fs) visible
-        const bool more = j0 + FT <= i0;
+    __syncthreads();                           // Us and Fs visible
+    for (;;) {
+        int j0n = j0, hfn = hf;
+        const bool more = advance(j0n, hfn);
+        const bool new_col = more && j0n != j0;
         if (more) {
-            fetch_u(j0 + FT);
-            if (j0 + FT == i0) fetch_c_diag(nxt, jold_n);
-            else fetch_c(nxt, jold_n);
-            jold_n = old_col(j0 + 2 * FT + jl);
+            if (new_col) {
+                fetch_u(j0n);
+                jold = old_col(j0n + jl);
+            }
+            fetch_tile(nxt, jold, j0n, hfn);
         }
         const int kl = lane >> 5, il = lane & 31;
+        const int rb = hf * FT;
 #pragma unroll
         for (int kk = 0; kk < nbp; kk += 2) {
-            float a0 = Fs[kk + kl][wm * 64 + il];
-            float a1 = Fs[kk + kl][wm * 64 + 32 + il];
+            float a0 = Fs[kk + kl][rb + wm * 64 + il];
+            float a1 = Fs[kk + kl][rb + wm * 64 + 32 + il];
             float b0 = Us[kk + kl][wn * 32 + il];
             acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0], 0, 0, 0);
             acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1], 0, 0, 0);
@@ -272,23 +299,28 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         // 16-byte slot of the row-quad layout
         const int jcol = j0 + jl;
         const int colB = (jcol < mn) ? jcol * 16 : kFar;
+        const bool on_diag = (j0 == i0 + rb);
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int qrow = i0 + wm * 64 + mt * 32 + 8 * q + lrow;   // first row of the quad
+                const int qrow = i0 + rb + wm * 64 + mt * 32 + 8 * q + lrow;   // first row of the quad
                 const int quad = qrow >> 2;
-                if (j0 == i0 && jcol > qrow + 3) continue;                  // wholly above the diagonal
+                if (on_diag && jcol > qrow + 3) continue;                   // wholly above the diagonal
                 uintx4 v4 = {__float_as_uint(acc[mt][4 * q]), __float_as_uint(acc[mt][4 * q + 1]),
                              __float_as_uint(acc[mt][4 * q + 2]), __float_as_uint(acc[mt][4 * q + 3])};
                 __builtin_amdgcn_raw_buffer_store_b128(v4, rnew, quad * ldn * 16 + colB, 0, 0);
             }
-        __syncthreads();                       // everyone is done reading Us
-        if (more) {
+        if (!more) break;
+        if (new_col) {
+            __syncthreads();                   // everyone is done reading Us
             stash_u();
-            acc[0] = nxt[0];
-            acc[1] = nxt[1];
+            __syncthreads();                   // the new Us visible
         }
+        acc[0] = nxt[0];
+        acc[1] = nxt[1];
+        j0 = j0n;
+        hf = hfn;
     }
 }
 
@@ -398,7 +430,8 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
         fa.A_new = bw.Abuf[nxt];
         fa.new_row_stride = mat_stride;
         fa.ld_new = m_next;
-        fa.strips = (m_next + FT - 1) / FT;
+        const int halves = (v->B <= 48) ? 2 : 1;    // LDS of two workgroups per CU allows tall strips up to K = 48
+        fa.strips = (m_next + halves * FT - 1) / (halves * FT);
         const int rows8 = (R + 7) / 8 * 8;
         {
             // one triangle of the surviving m_next x m_next part of every row's inverse is read and
@@ -407,11 +440,11 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
             obc_scope sc(ctx, OBC_KERNEL_FLUSH, (double)R * 8.0 * tri, (double)R * 2.0 * v->B * tri);
             const dim3 grid(fa.strips * rows8);
             switch (v->B) {
-            case 24: flush_kernel<24><<<grid, 512, 0, st>>>(fa); break;
-            case 36: flush_kernel<36><<<grid, 512, 0, st>>>(fa); break;
-            case 56: flush_kernel<56><<<grid, 512, 0, st>>>(fa); break;
-            case 48: flush_kernel<48><<<grid, 512, 0, st>>>(fa); break;
-            case 64: flush_kernel<64><<<grid, 512, 0, st>>>(fa); break;
+            case 24: flush_kernel<24, 2><<<grid, 512, 0, st>>>(fa); break;
+            case 36: flush_kernel<36, 2><<<grid, 512, 0, st>>>(fa); break;
+            case 48: flush_kernel<48, 2><<<grid, 512, 0, st>>>(fa); break;
+            case 56: flush_kernel<56, 1><<<grid, 512, 0, st>>>(fa); break;
+            case 64: flush_kernel<64, 1><<<grid, 512, 0, st>>>(fa); break;
             default: return obc_fail(ctx, OBC_ERR_BAD_ARG, "row solver: no flush kernel for block size %d", v->B);
             }
         }
