@@ -45,6 +45,8 @@ struct PanelShared {
     int pivs[BMAX];
     double bc_g, bc_invapp;
     int bc_o, bc_ok;
+    float bc_loss, bc_target;   // the step's records, written out after the barrier
+    int bc_code;
     double blk_loss;   // block pruning: loss of the block being eliminated, summed over its weights
 };
 
@@ -250,21 +252,24 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
     const bool owner = (tid == p % T);
     if (owner) {
         const int ep = p / T;
-        double wp = 0.0, ap = 1.0;
+        double wp = 0.0, ap = 1.0, target = 0.0, code = 0.0;
         int op = 0;
 #pragma unroll
         for (int e = 0; e < EPT; ++e)
             if (e == ep) { wp = st.w[e]; ap = st.dg[e]; op = st.og[e]; }
-        double target = 0.0, code = 0.0;
         if (op < 0) target = wp;
         else if (MODE == MODE_QUANT) {
-            code = rint((wp - pr.qo) / pr.qd);
+            code = rint((wp - pr.qo) * pr.iqd);   // same expression as in the selection
             code = fmin(fmax(code, 0.0), pr.qmax);
             target = pr.qo + pr.qd * code;
         }
         const bool ok = (ap > 0.0) && (ap < __builtin_inf());
-        const double invapp = 1.0 / ap;
-        sh.bc_g = (wp - target) / ap;
+        const double invapp = 1.0 / ap;           // the step's only division
+        const double er = target - wp;
+        sh.bc_loss = (float)(0.5 * er * er * invapp);
+        sh.bc_target = (float)target;
+        sh.bc_code = (int)code;
+        sh.bc_g = (wp - target) * invapp;
         sh.bc_invapp = invapp;
         sh.bc_o = op;
         sh.bc_ok = ok ? 1 : 0;
@@ -283,33 +288,33 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
             sh.cvec[r] = __fmul_rn(ur, sh.invd_s[r]);
         }
         if (a.nm_m > 0 && op >= 0) blk[op / a.nm_m] += 1;
-        if (MODE == MODE_BLOCK) {
-            // the block's loss is the sum of its four single losses (owners of consecutive steps
-            // are separated by the step's barriers)
-            const double l = wp * wp / (2.0 * ap);
-            const double acc = (S % 4 == 0) ? l : sh.blk_loss + l;
-            sh.blk_loss = acc;
-            if (ok) {
-                a.W_out[(size_t)pr.row * pr.d + op] = 0.f;
-                if (S % 4 == 3) {
-                    const int t = (pr.done + S) / 4;
-                    a.order[(size_t)pr.row * a.out_ld + t] = op / 4;
-                    a.loss[(size_t)pr.row * a.out_ld + t] = (float)acc;
-                }
-            }
-        } else if (ok && op >= 0) {
-            const int t = pr.done + S - pr.ndead;
-            const double er = target - wp;
-            a.order[(size_t)pr.row * a.out_ld + t] = op;
-            a.loss[(size_t)pr.row * a.out_ld + t] = (float)(er * er / (2.0 * ap));
-            a.W_out[(size_t)pr.row * pr.d + op] = (float)target;
-            if (MODE == MODE_QUANT) a.codes[(size_t)pr.row * pr.d + op] = (int)code;
-        }
     }
     OBC_TICK(3);   // cross-wave reduction, load issue, owner's publication
     __syncthreads();
     OBC_TICK(4);   // barrier 2
     if (!sh.bc_ok) return 2;
+    // the step's records are written here, while everybody waits for the fetched row anyway
+    if (owner) {
+        const int op = sh.bc_o;
+        if (MODE == MODE_BLOCK) {
+            // the block's loss is the sum of its four single losses (owners of consecutive steps
+            // are separated by the step's barriers)
+            const double acc = (S % 4 == 0) ? (double)sh.bc_loss : sh.blk_loss + (double)sh.bc_loss;
+            sh.blk_loss = acc;
+            a.W_out[(size_t)pr.row * pr.d + op] = 0.f;
+            if (S % 4 == 3) {
+                const int t = (pr.done + S) / 4;
+                a.order[(size_t)pr.row * a.out_ld + t] = op / 4;
+                a.loss[(size_t)pr.row * a.out_ld + t] = (float)acc;
+            }
+        } else if (op >= 0) {
+            const int t = pr.done + S - pr.ndead;
+            a.order[(size_t)pr.row * a.out_ld + t] = op;
+            a.loss[(size_t)pr.row * a.out_ld + t] = sh.bc_loss;
+            a.W_out[(size_t)pr.row * pr.d + op] = sh.bc_target;
+            if (MODE == MODE_QUANT) a.codes[(size_t)pr.row * pr.d + op] = sh.bc_code;
+        }
+    }
     const double g = sh.bc_g, invapp = sh.bc_invapp;
     const bool isdead = sh.bc_o < 0;
     // coefficients of this step, once, into registers
@@ -413,7 +418,7 @@ __global__ __launch_bounds__(T) void panel_kernel(PanelArgs a)
     pr.Acur = a.A_cur + (size_t)row * a.a_row_stride;
     pr.ld = a.ld;
     pr.swz = a.swz;
-    pr.gU = a.ws.U + (size_t)row * BMAX * d;
+    pr.gU = a.ws.U + (size_t)row * BMAX * a.ws.ldu;
     double *gw = a.ws.w + (size_t)row * d;
     double *gd = a.ws.diag + (size_t)row * d;
     int *go = a.ws.orig + (size_t)row * d;
@@ -479,7 +484,7 @@ __global__ __launch_bounds__(T) void panel_kernel(PanelArgs a)
 #pragma unroll
             for (int r = 0; r < B; ++r)
                 if (r < nbv)
-                    pr.gU[(size_t)r * d + jn] = (r < BR) ? st.u[r < BR ? r : 0][e] : ul[(r - BR) * (T * EPT) + j];
+                    pr.gU[(size_t)r * a.ws.ldu + jn] = (r < BR) ? st.u[r < BR ? r : 0][e] : ul[(r - BR) * (T * EPT) + j];
         }
     }
     for (int b = tid; b < nmb; b += T) a.ws.blk[(size_t)row * d + b] = blk[b];

@@ -27,7 +27,8 @@ __host__ __device__ inline size_t quad_index(int i, int j, int ld)
 
 struct BlockedWs {
     float *Abuf[2];     // R x d x d each
-    float *U;           // R x BMAX x d
+    float *U;           // R x BMAX x ldu
+    int ldu;            // leading dimension of U: d rounded up to a multiple of 4 (16-byte rows)
     float *invd;        // R x BMAX
     int *piv;           // R x BMAX  (compact index of each pivot of the current block)
     int *map;           // R x d     (new compact index -> old compact index)

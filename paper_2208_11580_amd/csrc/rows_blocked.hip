@@ -46,7 +46,8 @@ size_t carve(BlockedWs *ws, void *base, int R, int d)
     };
     size_t mat = (size_t)R * obc_align_up((size_t)d * d, 4) * sizeof(float);
     char *p0 = take(mat), *p1 = take(mat);
-    char *pu = take((size_t)R * BMAX * d * sizeof(float));
+    const int ldu = (d + 3) & ~3;
+    char *pu = take((size_t)R * BMAX * ldu * sizeof(float));
     char *pi = take((size_t)R * BMAX * sizeof(float));
     char *pp = take((size_t)R * BMAX * sizeof(int));
     char *pm = take((size_t)R * d * sizeof(int));
@@ -58,7 +59,7 @@ size_t carve(BlockedWs *ws, void *base, int R, int d)
     char *s4 = take((size_t)R * sizeof(int));
     char *pb = take((size_t)R * d);
     if (ws) {
-        ws->Abuf[0] = (float *)p0; ws->Abuf[1] = (float *)p1; ws->U = (float *)pu;
+        ws->Abuf[0] = (float *)p0; ws->Abuf[1] = (float *)p1; ws->U = (float *)pu; ws->ldu = ldu;
         ws->invd = (float *)pi; ws->piv = (int *)pp; ws->map = (int *)pm; ws->w = (double *)pw;
         ws->diag = (double *)pd; ws->orig = (int *)po; ws->m = (int *)s0; ws->done = (int *)s1;
         ws->total = (int *)s2; ws->ndead = (int *)s3; ws->nb = (int *)s4; ws->blk = (uint8_t *)pb;
@@ -172,7 +173,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 
     const int d = a.d;
     const int *map = a.ws.map + (size_t)row * d;
-    const float *U = a.ws.U + (size_t)row * BMAX * d;      // u_k in the new compact order
+    const int ldu = a.ws.ldu;
+    const float *U = a.ws.U + (size_t)row * BMAX * ldu;    // u_k in the new compact order, 16-byte aligned rows
     const float *invd = a.ws.invd + (size_t)row * BMAX;
     const int ldo = a.ld_old, ldn = a.ld_new;
     constexpr int nbp = (nb + 1) & ~1;
@@ -193,7 +195,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         int k = idx / SR, i = idx % SR;
         int ii = i0 + i;
         float v = 0.f;
-        if (k < nb && ii < mn) v = -__fmul_rn(U[(size_t)k * d + ii], invd[k]);
+        if (k < nb && ii < mn) v = -__fmul_rn(U[(size_t)k * ldu + ii], invd[k]);
         Fs[k][i] = v;
     }
     for (int i = tid; i < SR; i += 512) {
@@ -202,22 +204,26 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         rowoff_s[i] = (o < 0) ? kFar : swz ? ((o >> 2) * ldo * 4 + (o & 3)) * 4 : o * ldo * 4;
     }
 
-    // U tile staging: KMAX x 128 floats by 512 threads
-    constexpr int UPT = KMAX * FT / 512;
-    float ureg[UPT];
+    // U tile staging: KMAX x 128 floats by 512 threads, four consecutive columns (16 bytes) each
+    constexpr int UV = (KMAX * (FT / 4) + 511) / 512;
+    float4 ureg[UV];
     auto fetch_u = [&](int j0) {
 #pragma unroll
-        for (int h = 0; h < UPT; ++h) {
+        for (int h = 0; h < UV; ++h) {
             int idx = tid + h * 512;
-            int k = idx / FT, j = idx % FT;
-            ureg[h] = (k < nb && j0 + j < mn) ? U[(size_t)k * d + j0 + j] : 0.f;
+            int k = idx / (FT / 4), j = (idx % (FT / 4)) * 4;
+            // a group that starts below mn may end beyond it: those columns hold old values of
+            // the same buffer and only reach outputs that are never stored
+            ureg[h] = (k < nb && j0 + j < mn) ? *reinterpret_cast<const float4 *>(U + (size_t)k * ldu + j0 + j)
+                                               : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     };
     auto stash_u = [&]() {
 #pragma unroll
-        for (int h = 0; h < UPT; ++h) {
+        for (int h = 0; h < UV; ++h) {
             int idx = tid + h * 512;
-            Us[idx / FT][idx % FT] = ureg[h];
+            int k = idx / (FT / 4), j = (idx % (FT / 4)) * 4;
+            if (KMAX * (FT / 4) % 512 == 0 || k < KMAX) *reinterpret_cast<float4 *>(&Us[k][j]) = ureg[h];
         }
     };
     floatx16 acc[2], nxt[2];
@@ -430,7 +436,8 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
         fa.A_new = bw.Abuf[nxt];
         fa.new_row_stride = mat_stride;
         fa.ld_new = m_next;
-        const int halves = (v->B <= 48) ? 2 : 1;    // LDS of two workgroups per CU allows tall strips up to K = 48
+        // rows per strip, in 128-row halves: as tall as two workgroups' F tiles allow in a CU's LDS
+        const int halves = (v->B <= 48) ? 2 : 1;
         fa.strips = (m_next + halves * FT - 1) / (halves * FT);
         const int rows8 = (R + 7) / 8 * 8;
         {
