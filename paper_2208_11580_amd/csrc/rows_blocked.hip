@@ -154,8 +154,8 @@ template <int KMAX, int HALVES>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) void flush_kernel(FlushArgs a)
 {
     constexpr int SR = HALVES * FT;          // rows per strip
-    __shared__ float Fs[KMAX][SR + 4];
-    __shared__ float Us[KMAX][FLD];
+    __shared__ __align__(16) float Fs[KMAX][SR + 4];
+    __shared__ __align__(16) float Us[KMAX][FLD];
     __shared__ int rowoff_s[SR];   // byte offset of each strip row in the old matrix
     __shared__ int rowold_s[SR];   // its old compact index
 
@@ -190,13 +190,18 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     const int jl = wn * 32 + (lane & 31);
     const int lrow = 4 * (lane >> 5);        // the lane-dependent part of the accumulator row
 
-    // F tile: F[k][i] = -u_k[i] / a_k for the strip's rows; byte offsets of the strip's old rows
-    for (int idx = tid; idx < nbp * SR; idx += 512) {
-        int k = idx / SR, i = idx % SR;
+    // F tile: F[k][i] = -u_k[i] / a_k for the strip's rows (four rows per 16-byte load; rows
+    // beyond mn only reach outputs that are never stored); byte offsets of the strip's old rows
+    for (int idx = tid; idx < nbp * (SR / 4); idx += 512) {
+        int k = idx / (SR / 4), i = (idx % (SR / 4)) * 4;
         int ii = i0 + i;
-        float v = 0.f;
-        if (k < nb && ii < mn) v = -__fmul_rn(U[(size_t)k * ldu + ii], invd[k]);
-        Fs[k][i] = v;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (k < nb && ii < mn) {
+            v = *reinterpret_cast<const float4 *>(U + (size_t)k * ldu + ii);
+            const float s = -invd[k];
+            v.x = __fmul_rn(v.x, s); v.y = __fmul_rn(v.y, s); v.z = __fmul_rn(v.z, s); v.w = __fmul_rn(v.w, s);
+        }
+        *reinterpret_cast<float4 *>(&Fs[k][i]) = v;
     }
     for (int i = tid; i < SR; i += 512) {
         int o = (i0 + i < mn) ? map[i0 + i] : -1;
