@@ -7,8 +7,8 @@
 // 1e4..1e5; an fp32 factorisation would already cost three to four digits of H^-1).
 //
 //   1. A = double(H);  blocked right-looking Cholesky A = L L^T with 64-wide block columns:
-//      the diagonal block is factored and inverted by a single wavefront that keeps it in
-//      registers (lane i owns row i; values move between lanes with v_readlane), the panel below
+//      the diagonal block is factored and inverted by a single wavefront (16 x 16 sub-blocks in
+//      registers, the rest of the block on the fp64 matrix core out of LDS), the panel below
 //      is a product with the inverted diagonal block, the trailing update is a tiled GEMM.
 //   2. Y = L^-1 by right-looking blocked forward substitution on the identity (two GEMMs per
 //      block row, each over the whole remaining matrix, so all CUs are busy).
@@ -42,62 +42,165 @@ __device__ __forceinline__ double readlane_f64(double v, int l)
     return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
 }
 
+// 1 / sqrt(x) in full fp64: hardware estimate and two Newton steps
+__device__ __forceinline__ double rsqrt_f64(double x)
+{
+    double r = __builtin_amdgcn_rsq(x);
+    r = r * (1.5 - 0.5 * x * r * r);
+    r = r * (1.5 - 0.5 * x * r * r);
+    return r;
+}
+
 // Factor the bs x bs (bs <= 64) diagonal block at A (leading dimension lda) in place (lower
 // triangle), and write the inverse of that triangular factor to Linv (NB x NB, row-major, zeros
-// above the diagonal).  One wavefront: lane i keeps row i of the block in registers; a block
-// smaller than 64 is padded with the identity.
+// above the diagonal).  A block smaller than 64 is padded with the identity.
+//
+// One wavefront, the block in LDS, worked on in 16 x 16 sub-blocks.  For each of the four block
+// columns: the diagonal sub-block is factored and its factor inverted in registers (lane i < 16
+// holds row i; values cross lanes with v_readlane), the sub-blocks below are multiplied by that
+// inverse and the trailing sub-blocks updated, both on the fp64 matrix core
+// (v_mfma_f64_16x16x4: lane l supplies a(i = l % 16, k = l / 16) and b(k = l / 16, j = l % 16)
+// and holds c(4 r + l / 16, l % 16) in accumulator register r).  The off-diagonal sub-blocks of
+// L^-1 then follow from  T_is = -T_ii sum_{s <= k < i} L_ik T_ks.
 __global__ __launch_bounds__(64) void potrf_wave_kernel(double *__restrict__ A, int lda, int bs,
                                                         double *__restrict__ Linv, int *status)
 {
-    __shared__ double Ls[NB][NB + 1];
-    const int lane = threadIdx.x;
-    // coalesced load through LDS, then row `lane` into registers
+    constexpr int PL = NB + 1;
+    constexpr int SB = 16;                    // sub-block edge
+    __shared__ double Ls[NB * PL];            // the block; becomes L (lower triangle)
+    __shared__ double Ts[NB * PL];            // L^-1
+    __shared__ double Xs[SB * (SB + 1)];
+    const int lane = threadIdx.x, l16 = lane & 15, lg = lane >> 4;
 #pragma unroll 4
     for (int i = 0; i < NB; ++i) {
         double v = (i == lane) ? 1.0 : 0.0;
         if (i < bs && lane <= i) v = A[(int64_t)i * lda + lane];
-        Ls[i][lane] = v;
+        Ls[i * PL + lane] = v;
+        Ts[i * PL + lane] = 0.0;
     }
     __syncthreads();
-    double row[NB];
-#pragma unroll
-    for (int c = 0; c < NB; ++c) row[c] = Ls[lane][c];
 
     bool bad = false;
 #pragma unroll
-    for (int j = 0; j < NB; ++j) {
-        double pj = readlane_f64(row[j], j);
-        if (!(pj > 0.0) || !(pj < __builtin_inf())) { bad = true; pj = 1.0; }
-        const double ljj = sqrt(pj);
-        const double cj = row[j] / ljj;
-        row[j] = (lane == j) ? ljj : (lane > j ? cj : row[j]);
-        const double mine = (lane > j) ? row[j] : 0.0;     // L[lane][j], 0 on and above the diagonal
+    for (int s = 0; s < NB / SB; ++s) {
+        const int o = SB * s;
+        // (an opaque copy of the lane index per block column: otherwise the lane masks below are
+        // shared by the four unrolled block columns and stay live in scalar registers throughout)
+        int l16s = l16;
+        asm volatile("" : "+v"(l16s));
+        // ---- diagonal sub-block: row (o + l16) in registers (lanes >= 16 duplicate lanes < 16)
+        double row[SB], rj[SB], t[SB];
 #pragma unroll
-        for (int c = j + 1; c < NB; ++c) {
-            const double lcj = readlane_f64(row[j], c);     // L[c][j]
-            const double f = (lane >= c) ? mine : 0.0;
-            row[c] = fma(-f, lcj, row[c]);
+        for (int c = 0; c < SB; ++c) row[c] = Ls[(o + l16) * PL + o + c];
+#pragma unroll
+        for (int j = 0; j < SB; ++j) {
+            double pj = readlane_f64(row[j], j);
+            if (!(pj > 0.0) || !(pj < __builtin_inf())) { bad = true; pj = 1.0; }
+            const double r = rsqrt_f64(pj);
+            rj[j] = r;                                          // 1 / L[j][j]
+            const double cj = row[j] * r;
+            row[j] = (l16s == j) ? pj * r : (l16s > j ? cj : 0.0);
+            const double mine = (l16s > j) ? cj : 0.0;          // L[l16][j] below the diagonal
+#pragma unroll
+            for (int c = j + 1; c < SB; ++c) {
+                const double lcj = readlane_f64(cj, c);         // L[c][j]
+                row[c] = fma(-mine, lcj, row[c]);
+                // pin the update here: left to itself the compiler defers it to the column's
+                // turn and keeps every L[c][j] alive in scalar registers until then
+                asm volatile("" : "+v"(row[c]));
+            }
         }
+        // ---- inverse of the 16 x 16 factor, lane c computes column c:
+        //      t[i] = (delta_ic - sum_{k<i} L[i][k] t[k]) / L[i][i]
+#pragma unroll
+        for (int i = 0; i < SB; ++i) {
+            double acc = (l16s == i) ? 1.0 : 0.0;
+            // the lane to read from, made to depend on the previous row's result: otherwise
+            // the lane reads of all rows are issued up front and overflow the scalar registers
+            int sel = i;
+            if (i > 0) asm volatile("" : "+s"(sel) : "v"(t[i > 0 ? i - 1 : 0]));
+#pragma unroll
+            for (int k = 0; k < i; ++k) acc = fma(-readlane_f64(row[k], sel), t[k], acc);
+            t[i] = acc * rj[i];
+        }
+        if (lane < SB) {
+#pragma unroll
+            for (int c = 0; c < SB; ++c) {
+                Ls[(o + lane) * PL + o + c] = row[c];
+                Ts[(o + c) * PL + o + lane] = t[c];
+            }
+        }
+        __syncthreads();
+        // ---- sub-blocks below: L_is = A_is T_ss^T
+        doublex4 P[NB / SB];
+#pragma unroll
+        for (int ib = s + 1; ib < NB / SB; ++ib) {
+            doublex4 acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int kc = 0; kc < SB / 4; ++kc) {
+                const double av = Ls[(SB * ib + l16) * PL + o + 4 * kc + lg];
+                const double bv = Ts[(o + l16) * PL + o + 4 * kc + lg];
+                acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+            }
+            P[ib] = acc;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ib = s + 1; ib < NB / SB; ++ib)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) Ls[(SB * ib + 4 * r + lg) * PL + o + l16] = P[ib][r];
+        __syncthreads();
+        // ---- trailing sub-blocks: A_ij -= L_is L_js^T  (s < j <= i)
+#pragma unroll
+        for (int ib = s + 1; ib < NB / SB; ++ib)
+#pragma unroll
+            for (int jb = s + 1; jb <= ib; ++jb) {
+                doublex4 acc;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[r] = Ls[(SB * ib + 4 * r + lg) * PL + SB * jb + l16];
+#pragma unroll
+                for (int kc = 0; kc < SB / 4; ++kc) {
+                    const double av = -Ls[(SB * ib + l16) * PL + o + 4 * kc + lg];
+                    const double bv = Ls[(SB * jb + l16) * PL + o + 4 * kc + lg];
+                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) Ls[(SB * ib + 4 * r + lg) * PL + SB * jb + l16] = acc[r];
+            }
+        __syncthreads();
     }
-    // the factor goes to LDS: the inverse below reads it from there (uniform addresses), which
-    // frees the registers that held the rows
-    __syncthreads();
+    // ---- off-diagonal sub-blocks of T = L^-1, block column by block column, top to bottom
 #pragma unroll
-    for (int c = 0; c < NB; ++c) Ls[lane][c] = row[c];
-    __syncthreads();
-    // T = L^-1, lane c computes column c:  T[i][c] = (delta_ic - sum_{k<i} L[i][k] T[k][c]) / L[i][i]
-    double t[NB];
+    for (int s = 0; s + 1 < NB / SB; ++s)
 #pragma unroll
-    for (int i = 0; i < NB; ++i) {
-        double acc = (lane == i) ? 1.0 : 0.0;
+        for (int ib = s + 1; ib < NB / SB; ++ib) {
+            doublex4 x = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-        for (int k = 0; k < i; ++k) acc = fma(-Ls[i][k], t[k], acc);
-        t[i] = acc / Ls[i][i];
-    }
+            for (int kb = s; kb < ib; ++kb)
+#pragma unroll
+                for (int kc = 0; kc < SB / 4; ++kc) {
+                    const double av = Ls[(SB * ib + l16) * PL + SB * kb + 4 * kc + lg];
+                    const double bv = Ts[(SB * kb + 4 * kc + lg) * PL + SB * s + l16];
+                    x = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, x, 0, 0, 0);
+                }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) Xs[(4 * r + lg) * (SB + 1) + l16] = x[r];
+            __syncthreads();
+            doublex4 y = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int kc = 0; kc < SB / 4; ++kc) {
+                const double av = -Ts[(SB * ib + l16) * PL + SB * ib + 4 * kc + lg];
+                const double bv = Xs[(4 * kc + lg) * (SB + 1) + l16];
+                y = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, y, 0, 0, 0);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) Ts[(SB * ib + 4 * r + lg) * PL + SB * s + l16] = y[r];
+            __syncthreads();
+        }
 #pragma unroll 4
     for (int i = 0; i < NB; ++i) {
-        if (i < bs && lane <= i) A[(int64_t)i * lda + lane] = Ls[i][lane];
-        Linv[i * NB + lane] = (lane <= i) ? t[i] : 0.0;
+        if (i < bs && lane <= i) A[(int64_t)i * lda + lane] = Ls[i * PL + lane];
+        Linv[i * NB + lane] = (lane <= i) ? Ts[i * PL + lane] : 0.0;
     }
     if (lane == 0 && bad) obc_latch(status, OBC_ERR_NOT_SPD);
 }
