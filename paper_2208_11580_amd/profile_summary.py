@@ -4,6 +4,12 @@
     python -m paper_2208_11580_amd.profile_summary traffic <fetch_counter_collection.csv> <write_counter_collection.csv> \
                                                            <workload> <command> > profiles/<name>.txt
 
+    python -m paper_2208_11580_amd.profile_summary counters <title> <command> <counter_collection.csv>... > profiles/<name>.txt
+
+`counters` lists, per kernel, every counter found in the given runs (one run per counter set):
+percent-type derived metrics (names ending in Util / Busy / Stalled) are averaged over the launches,
+everything else is summed.
+
 `traffic` scales the FETCH_SIZE / WRITE_SIZE counters (KiB per dispatch) by what the same counter
 reads for the plain 1 GiB device copy that `bench.py --calib-copy` appends to the run (the copy
 reads 1 GiB and writes 1 GiB), and reports the HBM bytes per launch of every row-solver kernel.
@@ -84,9 +90,50 @@ def traffic(fetch_csv, write_csv, workload, command):
             family, a[0], a[1] / a[0], a[1] / (a[2] * 1e-3) / 1e9))
 
 
+def counters(title, command, paths):
+    per = collections.OrderedDict()          # kernel -> counter -> [n, sum]
+    launches = collections.OrderedDict()     # kernel -> (dispatch ids, ms)
+    names = []
+    for path in paths:
+        seen = set()
+        for r in csv.DictReader(open(path)):
+            k = _short(r["Kernel_Name"])
+            c = r["Counter_Name"]
+            if c not in names:
+                names.append(c)
+            a = per.setdefault(k, {}).setdefault(c, [0, 0.0])
+            a[0] += 1
+            a[1] += float(r["Counter_Value"])
+            if path == paths[0] and (k, r["Dispatch_Id"]) not in seen:
+                seen.add((k, r["Dispatch_Id"]))
+                l = launches.setdefault(k, [0, 0.0])
+                l[0] += 1
+                l[1] += (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e6
+    print(title)
+    print("commands (one run per counter set, from /tmp on the MI355X box):")
+    for c in command.split(" ;; "):
+        print("    " + c)
+    print("percent-type metrics are averaged over the launches, the others summed; ms is the first run's")
+    print("%-40s %8s %9s " % ("kernel", "launches", "ms") + " ".join("%16s" % n[-16:] for n in names))
+    for k, cs in per.items():
+        if k not in launches:
+            continue
+        vals = []
+        for n in names:
+            if n not in cs:
+                vals.append("%16s" % "-")
+            elif n.endswith(("Util", "Busy", "Stalled")):
+                vals.append("%16.2f" % (cs[n][1] / cs[n][0]))
+            else:
+                vals.append("%16.4g" % cs[n][1])
+        print("%-40s %8d %9.3f " % (k[:40], launches[k][0], launches[k][1]) + " ".join(vals))
+
+
 if __name__ == "__main__":
     if len(sys.argv) >= 6 and sys.argv[1] == "stats":
         stats(sys.argv[2], int(sys.argv[3]), sys.argv[4], sys.argv[5])
+    elif len(sys.argv) >= 5 and sys.argv[1] == "counters":
+        counters(sys.argv[2], sys.argv[3], sys.argv[4:])
     elif len(sys.argv) >= 6 and sys.argv[1] == "traffic":
         traffic(sys.argv[2], sys.argv[3], sys.argv[4], sys.argv[5])
     else:
