@@ -53,6 +53,22 @@ def test_host_only_calls(lib):
     assert lib.obc_hessian_workspace_bytes(576, 50000, ctypes.byref(n)) == 0 and n.value >= 576 * 576 * 4
     assert lib.obc_global_select_workspace_bytes(64, 576, ctypes.byref(n)) == 0 and n.value >= 64 * 576 * 4
     assert lib.obc_last_error(None) == b"null context"
+    # widened entry points
+    assert lib.obc_cross_workspace_bytes(256, 2304, 50000, ctypes.byref(n)) == 0 and n.value >= 256 * 2304 * 4
+    assert lib.obc_cross_workspace_bytes(0, 2304, 50000, ctypes.byref(n)) == -1
+    m = ctypes.c_size_t()
+    assert lib.obc_invert_workspace_bytes(576, ctypes.byref(m)) == 0
+    assert lib.obc_refit_workspace_bytes(576, 64, ctypes.byref(n)) == 0 and n.value >= m.value + 2 * 64 * 576 * 8
+    assert lib.obc_refit_workspace_bytes(576, 0, ctypes.byref(n)) == -1
+    # block pruning: blocks of 4 go to the deferred-update solver, other sizes to the rank-1 solver,
+    # which cannot be forced to take what it does not do
+    r1, rb = ctypes.c_size_t(), ctypes.c_size_t()
+    assert lib.obc_rows_workspace_bytes(8, 576, 1, ctypes.byref(r1)) == 0
+    assert lib.obc_rows_workspace_bytes(8, 576, 2, ctypes.byref(rb)) == 0
+    assert lib.obc_blocks_workspace_bytes(8, 576, 4, 0, ctypes.byref(n)) == 0 and n.value == rb.value
+    assert lib.obc_blocks_workspace_bytes(8, 576, 2, 0, ctypes.byref(n)) == 0 and n.value == r1.value
+    assert lib.obc_blocks_workspace_bytes(8, 576, 2, 2, ctypes.byref(n)) == -1
+    assert lib.obc_blocks_workspace_bytes(8, 576, 9, 0, ctypes.byref(n)) == -1
 
 
 def test_no_oracle_in_product_path():

@@ -474,6 +474,34 @@ def test_end_to_end_tiny_layer(obc, orc):
     assert np.linalg.norm(_np(What) - Wo) <= 1e-4 * np.linalg.norm(Wo)
 
 
+def test_many_sparsity_levels_from_one_trace(obc, orc):
+    """The paper's database of sparsity levels s_i = 1 - (1 - delta)^i (Sec. 6) comes from ONE run of
+    the row solver: every level is a global step over the same loss traces and a gather from the
+    same weight trace.  Each level is checked against the oracle's replay of its own traces."""
+    W, X = _layer("conv64x576", d_col=96, d_row=24, n_samples=800)
+    Hinv = _hinv(obc, X)
+    res = obc.obc_prune_rows(W, Hinv, want_trace=True)
+    obc.obc_check()
+    R, d = W.shape
+    A, Wn = _np(Hinv).astype(np.float64), _np(W).astype(np.float64)
+    ro = orc.prune_rows(A, Wn)
+    assert np.array_equal(ro["order"], _np(res["order"]))       # no near ties in this layer
+    levels = [1.0 - 0.9 ** i for i in range(1, 31, 3)]
+    prev = -1
+    for sp in levels:
+        k = obc_inputs.target_count(sp, R, d)
+        assert k > prev
+        prev = k
+        counts, mask = obc.obc_global_select(res["loss"], res["order"], k)
+        What = obc.obc_gather_trace(W, res["trace"], counts)
+        # Alg. 2 on the GPU's own (fp32) traces: the counts are then an exact integer comparison
+        co = orc.global_select(_np(res["loss"]).astype(np.float64), k)
+        assert np.array_equal(_np(counts), co), sp
+        assert int(mask.sum()) == k and int((What == 0).sum()) >= k
+        Wo = orc.reconstruct(A, Wn, co)
+        assert np.linalg.norm(_np(What) - Wo) <= 1e-4 * np.linalg.norm(Wo), sp
+
+
 @pytest.mark.parametrize("strategy", [1, 2])
 def test_rows_that_do_no_step_keep_their_weights(obc, strategy):
     W, X = _layer("conv64x576", d_col=280, d_row=5, n_samples=1500)
