@@ -113,6 +113,12 @@ int obc_rows_workspace_bytes(int R, int d, int strategy, size_t *bytes);
  *            indices has fewer than nm_m - nm_n pruned weights; nm_m == 0: unstructured
  *   stop_counts  nullable, R: row i stops after min(k_steps, stop_counts[i]) steps (replay of
  *            the counts chosen by obc_global_select); entries of order/loss beyond are untouched
+ *   live     nullable, R x d: 0 marks a weight that is already pruned (Sec. 4 "Implementation
+ *            Details": an already sparse matrix is handled on the dense sub-problem of its
+ *            non-zeros).  Those indices are first removed from the row's inverse (Lemma 1, no
+ *            weight change, nothing recorded), keep weight 0, and the k_steps greedy steps run
+ *            on the survivors (a row with fewer survivors stops when none is left; entries of
+ *            order / loss beyond are untouched).  Not combined with the N:M rule.
  *   order    R x k_steps int32 out: index pruned at each step
  *   loss     R x k_steps fp32 out: loss change w_p^2 / (2 [H^-1]_pp) of each step
  *   W_out    R x d out: the row after its last step (pruned weights exactly 0)
@@ -120,8 +126,8 @@ int obc_rows_workspace_bytes(int R, int d, int strategy, size_t *bytes);
  *            Sec. 4 Step 2, kept in HBM here)
  * Ties in the argmin go to the lowest index. */
 int obc_prune_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d, int k_steps,
-                   int nm_n, int nm_m, const int32_t *stop_counts, int32_t *order, float *loss,
-                   float *W_out, float *trace, int strategy, void *ws, size_t ws_bytes);
+                   int nm_n, int nm_m, const int32_t *stop_counts, const uint8_t *live, int32_t *order,
+                   float *loss, float *W_out, float *trace, int strategy, void *ws, size_t ws_bytes);
 
 /* Block pruning (Sec. 4 "Block-Sparsity", eq. (5)): Algorithm 1 on blocks of c consecutive
  * weights (block b = indices b c .. b c + c - 1; d must be a multiple of c, 1 <= c <= 8).  Each

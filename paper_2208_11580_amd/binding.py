@@ -75,7 +75,7 @@ def load_library():
     lib.obc_invert_workspace_bytes.argtypes = [c_int, sp]
     lib.obc_invert.argtypes = [vp, vp, c_int, vp, c_size_t]
     lib.obc_rows_workspace_bytes.argtypes = [c_int, c_int, c_int, sp]
-    lib.obc_prune_rows.argtypes = [vp, vp, vp, c_int, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp,
+    lib.obc_prune_rows.argtypes = [vp, vp, vp, c_int, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp, vp,
                                    c_int, vp, c_size_t]
     lib.obc_blocks_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, sp]
     lib.obc_prune_blocks.argtypes = [vp, vp, vp, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp, c_int, vp, c_size_t]
@@ -224,7 +224,7 @@ class Context:
         return need.value
 
     def obc_prune_rows(self, W, Hinv, k_steps=None, nm=(0, 0), stop_counts=None, want_trace=False,
-                       strategy=STRATEGY_AUTO, out=None):
+                       strategy=STRATEGY_AUTO, out=None, live=None):
         R, d = W.shape
         if k_steps is None:
             k_steps = d if nm[1] == 0 else (d // nm[1]) * (nm[1] - nm[0])
@@ -246,7 +246,8 @@ class Context:
         ws = self.workspace(self.rows_workspace_bytes(R, d, strategy))
         self._ck(self.lib.obc_prune_rows(
             self.h, _ptr(W, torch.float32), _ptr(Hinv, torch.float32), R, d, int(k_steps), int(nm[0]),
-            int(nm[1]), _ptr(stop_counts, torch.int32), _ptr(order), _ptr(loss), _ptr(W_out), _ptr(trace),
+            int(nm[1]), _ptr(stop_counts, torch.int32), _ptr(live, torch.uint8), _ptr(order), _ptr(loss),
+            _ptr(W_out), _ptr(trace),
             int(strategy), c_void_p(ws.data_ptr()), ws.numel()))
         return dict(order=order, loss=loss, W=W_out, trace=trace)
 

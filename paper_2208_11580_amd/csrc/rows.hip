@@ -6,7 +6,7 @@ namespace obc_rows {
 bool rank1_lds_resident(int d, int nm_m);
 size_t rank1_workspace_bytes(int R, int d);
 int rank1_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, int R, int d, int k_steps,
-                 int nm_n, int nm_m, const int32_t *stop_counts, const float *delta,
+                 int nm_n, int nm_m, int blk_c, const int32_t *stop_counts, const float *delta,
                  const float *offset, int maxq, const uint8_t *live, int flags, int32_t *order, float *loss,
                  int32_t *codes, float *W_out, float *trace, int out_ld, void *ws, size_t ws_bytes);
 size_t blocked_workspace_bytes(int R, int d);
@@ -98,8 +98,8 @@ int obc_rows_workspace_bytes(int R, int d, int strategy, size_t *bytes)
 }
 
 int obc_prune_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d, int k_steps,
-                   int nm_n, int nm_m, const int32_t *stop_counts, int32_t *order, float *loss,
-                   float *W_out, float *trace, int strategy, void *ws, size_t ws_bytes)
+                   int nm_n, int nm_m, const int32_t *stop_counts, const uint8_t *live, int32_t *order,
+                   float *loss, float *W_out, float *trace, int strategy, void *ws, size_t ws_bytes)
 {
     if (!ctx) return OBC_ERR_BAD_ARG;
     if (R < 0 || d <= 0 || k_steps < 0)
@@ -112,6 +112,8 @@ int obc_prune_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d
         return obc_fail(ctx, OBC_ERR_BAD_SHAPE, "obc_prune_rows: k_steps (%d) > d (%d)", k_steps, d);
     if (nm_m < 0 || nm_n < 0 || (nm_m > 0 && nm_n > nm_m) || nm_m > 255)
         return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_prune_rows: bad N:M pattern %d:%d", nm_n, nm_m);
+    if (nm_m > 0 && live)
+        return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_prune_rows: the N:M rule applies to dense rows (live must be null)");
     if (nm_m > 0) {
         if (d % nm_m != 0)
             return obc_fail(ctx, OBC_ERR_BAD_SHAPE, "obc_prune_rows: d (%d) is not a multiple of M (%d)", d, nm_m);
@@ -121,10 +123,10 @@ int obc_prune_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d
     if (R == 0) return OBC_OK;
     int s = pick_strategy(strategy, d);
     if (s == OBC_STRATEGY_RANK1)
-        return rank1_launch(ctx, MODE_PRUNE, W, Hinv, R, d, k_steps, nm_n, nm_m, stop_counts, nullptr,
-                            nullptr, 0, nullptr, 0, order, loss, nullptr, W_out, trace, k_steps, ws, ws_bytes);
+        return rank1_launch(ctx, MODE_PRUNE, W, Hinv, R, d, k_steps, nm_n, nm_m, 0, stop_counts, nullptr,
+                            nullptr, 0, live, 0, order, loss, nullptr, W_out, trace, k_steps, ws, ws_bytes);
     return blocked_launch(ctx, MODE_PRUNE, W, Hinv, R, d, k_steps, nm_n, nm_m, stop_counts, nullptr,
-                          nullptr, 0, nullptr, 0, order, loss, nullptr, W_out, trace, k_steps, ws, ws_bytes);
+                          nullptr, 0, live, 0, order, loss, nullptr, W_out, trace, k_steps, ws, ws_bytes);
 }
 
 int obc_prune_blocks(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d, int c, int k_blocks,
@@ -149,7 +151,7 @@ int obc_prune_blocks(obc_ctx *ctx, const float *W, const float *Hinv, int R, int
         return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_prune_blocks: the deferred-update solver handles blocks of 4 only");
     if (R == 0) return OBC_OK;
     if (s == OBC_STRATEGY_RANK1)
-        return rank1_launch(ctx, MODE_BLOCK, W, Hinv, R, d, k_blocks, 0, c, stop_counts, nullptr, nullptr, 0,
+        return rank1_launch(ctx, MODE_BLOCK, W, Hinv, R, d, k_blocks, 0, 0, c, stop_counts, nullptr, nullptr, 0,
                             nullptr, 0, order, loss, nullptr, W_out, trace, k_blocks, ws, ws_bytes);
     return blocked_launch(ctx, MODE_BLOCK, W, Hinv, R, d, k_blocks * 4, 0, 0, stop_counts, nullptr, nullptr, 0,
                           nullptr, 0, order, loss, nullptr, W_out, trace, k_blocks, ws, ws_bytes);
@@ -183,7 +185,7 @@ int obc_quant_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d
     if (R == 0) return OBC_OK;
     int s = pick_strategy(strategy, d);
     if (s == OBC_STRATEGY_RANK1)
-        return rank1_launch(ctx, MODE_QUANT, W, Hinv, R, d, d, 0, 0, nullptr, delta, offset, maxq, live,
+        return rank1_launch(ctx, MODE_QUANT, W, Hinv, R, d, d, 0, 0, 0, nullptr, delta, offset, maxq, live,
                             flags, order, loss, codes, W_out, nullptr, d, ws, ws_bytes);
     return blocked_launch(ctx, MODE_QUANT, W, Hinv, R, d, d, 0, 0, nullptr, delta, offset, maxq, live,
                           flags, order, loss, codes, W_out, nullptr, d, ws, ws_bytes);

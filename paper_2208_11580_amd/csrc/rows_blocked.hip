@@ -86,7 +86,7 @@ __global__ __launch_bounds__(256) void blocked_init_kernel(InitArgs a)
     __syncthreads();
     int dead_local = 0;
     for (int j = tid; j < d; j += 256) {
-        bool alive = (a.mode == MODE_QUANT && a.live_in) ? a.live_in[(size_t)row * d + j] != 0 : true;
+        bool alive = (a.mode != MODE_BLOCK && a.live_in) ? a.live_in[(size_t)row * d + j] != 0 : true;
         a.ws.w[(size_t)row * d + j] = alive ? (double)a.W[(size_t)row * d + j] : 0.0;
         a.ws.diag[(size_t)row * d + j] = (double)a.Hinv[(size_t)j * d + j];
         a.ws.orig[(size_t)row * d + j] = alive ? j : ~j;
@@ -98,14 +98,17 @@ __global__ __launch_bounds__(256) void blocked_init_kernel(InitArgs a)
     atomicAdd(&cnt, dead_local);
     __syncthreads();
     if (tid == 0) {
-        int total = a.k_steps;   // in single eliminations (block pruning: 4 per block step)
-        if (a.mode == MODE_QUANT) total = d;   // eliminations of the dead + one step per survivor
+        // steps on the survivors, in single eliminations (block pruning: 4 per block step); the
+        // eliminations of the already-pruned indices come on top
+        const int survivors = d - cnt;
+        int steps = (a.mode == MODE_QUANT) ? survivors : (a.k_steps < survivors ? a.k_steps : survivors);
         if (a.stop_counts) {
             int sc = a.stop_counts[row];
             sc = sc < 0 ? 0 : sc;
             if (a.mode == MODE_BLOCK) sc = sc > d / 4 ? d : sc * 4;
-            total = sc < total ? sc : total;
+            steps = sc < steps ? sc : steps;
         }
+        const int total = cnt + steps;
         a.ws.m[row] = d;
         a.ws.done[row] = 0;
         a.ws.total[row] = total;
@@ -408,7 +411,7 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
     FlushArgs fa;
     fa.d = d; fa.R = R; fa.ws = bw;
 
-    const int host_total = (mode == MODE_QUANT) ? d : k_steps;   // upper bound over the rows
+    const int host_total = (mode == MODE_QUANT || live) ? d : k_steps;   // upper bound over the rows
     const size_t lds_nm = nm_m > 0 ? obc_align_up((size_t)(d / nm_m), 16) : 0;
     const size_t mat_stride = obc_align_up((size_t)d * d, 4);   // floats between two rows' matrices
     int host_done = 0;

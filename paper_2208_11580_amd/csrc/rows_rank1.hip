@@ -116,7 +116,7 @@ __global__ __launch_bounds__(1024) void rows_rank1_kernel(Rank1Args a)
     const float *Hinv = a.Hinv;
     for (size_t e = tid; e < (size_t)d * d; e += nthr) A[e] = Hinv[e];
     for (int j = tid; j < d; j += nthr) {
-        bool alive = (MODE == MODE_QUANT && a.live_in) ? (a.live_in[(size_t)row * d + j] != 0) : true;
+        bool alive = (MODE != MODE_BLOCK && a.live_in) ? (a.live_in[(size_t)row * d + j] != 0) : true;
         w[j] = alive ? (double)a.W[(size_t)row * d + j] : 0.0;
         diag[j] = (double)Hinv[(size_t)j * d + j];
         pos[j] = alive ? 0 : 0xffff;
@@ -140,6 +140,7 @@ __global__ __launch_bounds__(1024) void rows_rank1_kernel(Rank1Args a)
 
     int steps = a.k_steps;   // block pruning: block steps
     if (MODE == MODE_QUANT) steps = m;
+    if (MODE == MODE_PRUNE && steps > m) steps = m;   // an already sparse row has fewer candidates
     if (a.stop_counts) {
         int sc = a.stop_counts[row];
         sc = sc < 0 ? 0 : sc;
@@ -333,14 +334,13 @@ size_t rank1_workspace_bytes(int R, int d)
 }
 
 int rank1_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, int R, int d, int k_steps,
-                 int nm_n, int nm_m, const int32_t *stop_counts, const float *delta,
+                 int nm_n, int nm_m, int blk_c, const int32_t *stop_counts, const float *delta,
                  const float *offset, int maxq, const uint8_t *live, int flags, int32_t *order, float *loss,
                  int32_t *codes, float *W_out, float *trace, int out_ld, void *ws, size_t ws_bytes)
 {
     Rank1Args a;
     a.outliers = (flags & OBC_QUANT_OUTLIERS) ? 1 : 0;
-    a.blk_c = (mode == MODE_BLOCK) ? nm_m : 0;   // block pruning passes its block size as nm_m
-    if (mode == MODE_BLOCK) nm_n = nm_m = 0;
+    a.blk_c = (mode == MODE_BLOCK) ? blk_c : 0;
     a.W = W; a.Hinv = Hinv; a.R = R; a.d = d; a.k_steps = k_steps; a.nm_n = nm_n; a.nm_m = nm_m;
     a.stop_counts = stop_counts; a.delta = delta; a.offset = offset; a.maxq = maxq; a.live_in = live;
     a.order = order; a.loss = loss; a.codes = codes; a.W_out = W_out; a.trace = trace;

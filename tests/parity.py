@@ -125,6 +125,9 @@ def check_row(orc, stats, mode, Hinv32, w32, g_order, g_loss, g_w, k_steps, nm=(
         assert np.array_equal(gw_l.astype(np.float32), deq)
     if g_trace is not None and mode == "prune":
         gt = np.asarray(g_trace[:k_steps], np.float64)
+        if sub:
+            assert np.all(gt[:, np.setdiff1d(np.arange(d), S)] == 0.0)
+            gt = gt[:, S]
         num = np.linalg.norm(gt - r.trace, axis=1)
         den = np.linalg.norm(r.trace, axis=1)
         ok = num <= W_RTOL * den + 1e-30

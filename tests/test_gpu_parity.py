@@ -474,6 +474,48 @@ def test_end_to_end_tiny_layer(obc, orc):
     assert np.linalg.norm(_np(What) - Wo) <= 1e-4 * np.linalg.norm(Wo)
 
 
+@pytest.mark.parametrize("strategy", [1, 2])
+def test_prune_rows_on_an_already_sparse_matrix(obc, orc, strategy):
+    """Sec. 4 "Implementation Details": an already sparse matrix is pruned further on the dense
+    sub-problem of its non-zeros.  The oracle works on that sub-problem directly (inverse of the
+    sub-Hessian); the GPU reaches it by eliminating the zeros from H^-1 first."""
+    d, k1, k2 = 260, 100, 60
+    W, X = _layer("conv64x576", d_col=d, d_row=4, n_samples=2000)
+    Hinv = _hinv(obc, X)
+    first = obc.obc_prune_rows(W, Hinv, k_steps=k1, strategy=strategy)
+    live = (first["W"] != 0).to(torch.uint8)
+    assert int(live.sum()) == 4 * (d - k1)
+    second = obc.obc_prune_rows(first["W"], Hinv, k_steps=k2, live=live, strategy=strategy, want_trace=True)
+    obc.obc_check()
+    A, W1 = _np(Hinv), _np(first["W"])
+    st = RowParity()
+    for i in range(4):
+        check_row(orc, st, "prune", A, W1[i], _np(second["order"][i]), _np(second["loss"][i]),
+                  _np(second["W"][i]), k2, live=_np(live[i]), g_trace=_np(second["trace"][i]))
+    print(st)
+    assert int((second["W"] == 0).sum()) == 4 * (k1 + k2)
+    # continuing from the reduced inverse is continuing the same greedy run: the one-pass run over
+    # k1 + k2 steps takes (up to near ties) the same weights next
+    one = obc.obc_prune_rows(W, Hinv, k_steps=k1 + k2, strategy=strategy)
+    same = (one["order"][:, k1:] == second["order"]).float().mean().item()
+    assert same > 0.9, same
+    assert torch.allclose(one["W"], second["W"], rtol=1e-3, atol=1e-5)
+    # a row with fewer survivors than k_steps stops when none is left
+    live2 = live.clone()
+    live2[1, 5:] = 0
+    W2 = first["W"] * live2
+    few = obc.obc_prune_rows(W2, Hinv, k_steps=k2, live=live2, strategy=strategy)
+    obc.obc_check()
+    assert torch.all(few["W"][1] == 0)
+    n1 = int(live2[1].sum())
+    assert torch.all(few["order"][1, n1:] == -1) and torch.all(few["order"][1, :n1] >= 0)
+    # not combined with N:M
+    import paper_2208_11580_amd as pkg
+    with pytest.raises(pkg.ObcError):
+        obc.obc_prune_rows(W[:, :256].contiguous(), Hinv[:256, :256].contiguous(), nm=(2, 4),
+                           live=live[:, :256].contiguous(), strategy=strategy)
+
+
 def test_many_sparsity_levels_from_one_trace(obc, orc):
     """The paper's database of sparsity levels s_i = 1 - (1 - delta)^i (Sec. 6) comes from ONE run of
     the row solver: every level is a global step over the same loss traces and a gather from the
@@ -556,3 +598,13 @@ def test_rows_many_more_rows_than_cus(obc, orc):
     assert torch.equal(srt, torch.arange(d, device="cuda", dtype=torch.int32).expand(R, d))
     assert torch.all(res["W"] == 0)
     _check_quant(obc, orc, W, Hinv, 4, 2, rows=rows)
+    # block pruning through the same shared-CU variant
+    kb = d // 4
+    blk = obc.obc_prune_blocks(W, Hinv, 4, strategy=2)
+    obc.obc_check()
+    A, Wn = _np(Hinv), _np(W)
+    for i in rows:
+        check_block_row(orc, A, Wn[i], 4, _np(blk["order"][i]), _np(blk["loss"][i]), _np(blk["W"][i]), kb)
+    srt = torch.sort(blk["order"], dim=1).values
+    assert torch.equal(srt, torch.arange(kb, device="cuda", dtype=torch.int32).expand(R, kb))
+    assert torch.all(blk["W"] == 0)
