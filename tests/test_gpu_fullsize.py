@@ -248,3 +248,31 @@ def test_conv256x2304_sequential_obq_with_outlier_heuristic(obc, orc):
         check_row(orc, st, "quant", A, _np(Wr[i]), _np(res["order"][i]), _np(res["loss"][i]), _np(res["W"][i]), d,
                   grid=(float(delta[i]), float(offset[i]), maxq), g_codes=_np(res["codes"][i]), outlier=True)
     print(st)
+
+
+def test_width_4608_first_blocks(obc, orc):
+    """The widest layer of the workloads (d_col = 4608) uses the panel variant with six owned
+    indices per thread and blocks of 24; the oracle replays the first 240 steps of one row."""
+    W, X, _ = obc_inputs.make_layer("conv512x4608", device="cuda", d_row=3, n_samples=12000)
+    R, d = W.shape
+    assert d == 4608
+    Hinv = obc.obc_invert(obc.obc_hessian(X))
+    k = 240
+    res = obc.obc_prune_rows(W, Hinv, k_steps=k)
+    obc.obc_check()
+    st = RowParity()
+    check_row(orc, st, "prune", _np(Hinv), _np(W[1]), _np(res["order"][1]), _np(res["loss"][1]),
+              _np(res["W"][1]), k)
+    print(st)
+    assert int((res["W"] == 0).sum()) == R * k
+    # OBQ over the same width: every weight ends on its grid value, the trace of loss changes sums
+    # to the quadratic form (checked in fp64 against H itself)
+    delta, offset, maxq = obc.obc_minmax_grid(W, 4)
+    q = obc.obc_quant_rows(W, Hinv, delta, offset, maxq)
+    obc.obc_check()
+    deq = (offset[:, None].double() + delta[:, None].double() * q["codes"].double()).float()
+    assert torch.equal(q["W"], deq)
+    H = torch.linalg.inv(Hinv.double())
+    dW = (W - q["W"]).double()
+    quad = 0.5 * ((dW @ H) * dW).sum(dim=1)
+    assert torch.allclose(q["loss"].double().sum(dim=1), quad, rtol=5e-3)
