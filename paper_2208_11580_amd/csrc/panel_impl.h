@@ -9,10 +9,13 @@ namespace obc_blocked {
 // Phase timing of the panel kernel for kernel development: compiled in only with
 // -DOBC_PANEL_TIMING; thread 0 of workgroup 0 accumulates shader-clock deltas per phase.
 #ifdef OBC_PANEL_TIMING
+#ifndef OBC_TICK_MIN_M
+#define OBC_TICK_MIN_M 0       // only launches with a live size above this are timed
+#endif
 extern __device__ unsigned long long obc_panel_timing[8];
 #define OBC_TICK(slot)                                                        \
     do {                                                                      \
-        if (blockIdx.x == 0 && threadIdx.x == 0) {                            \
+        if (blockIdx.x == 0 && threadIdx.x == 0 && pr.m > OBC_TICK_MIN_M) {   \
             unsigned long long now__ = __builtin_readcyclecounter();          \
             atomicAdd(&obc_panel_timing[slot], now__ - pr.tick);              \
             const_cast<PanelRow &>(pr).tick = now__;                          \
