@@ -240,10 +240,10 @@ def main():
         from oracle import oracle as orc
 
         threads = min(os.cpu_count() or 1, 16)
-        n_rows = args.cpu_rows or threads
-        n_rows = min(n_rows, R)
         # keep the sample to roughly 10-30 s: the oracle costs ~ k d^2 / 3 inner iterations per row
         per_row_s = (k_steps * (BC if task.startswith("block") else 1) * d * d / 3.0) / 0.7e9
+        n_rows = args.cpu_rows or threads * max(1, int(round(15.0 / max(per_row_s, 1e-9))))
+        n_rows = min(n_rows, R)
         while n_rows > threads and per_row_s * n_rows / threads > 30:
             n_rows //= 2
         A64 = H.cpu().numpy().astype(np.float64)
