@@ -256,7 +256,9 @@ __device__ __forceinline__ void gemm64_tile(const GemmArgs &g, int ti, int tj)
 
     const bool a_kfast = (as_k == 1);
     const bool b_jfast = (bs_j == 1);
-    for (int k0 = kbeg; k0 < K; k0 += GK) {
+    // the next k-slab is fetched into registers while the current one is multiplied
+    double ra[4], rb[4];
+    auto fetch = [&](int k0) {
 #pragma unroll
         for (int h = 0; h < 4; ++h) {
             int e = tid + h * 256;
@@ -264,14 +266,31 @@ __device__ __forceinline__ void gemm64_tile(const GemmArgs &g, int ti, int tj)
             if (a_kfast) { i = e / GK; k = e % GK; } else { k = e / NB; i = e % NB; }
             double v = 0.0;
             if (i0 + i < M && k0 + k < K) v = A[(int64_t)(i0 + i) * as_i + (int64_t)(k0 + k) * as_k];
-            As[k][i] = v;
+            ra[h] = v;
             int j, kb;
             if (b_jfast) { kb = e / NB; j = e % NB; } else { j = e / GK; kb = e % GK; }
             double u = 0.0;
             if (j0 + j < N && k0 + kb < K) u = B[(int64_t)(k0 + kb) * bs_k + (int64_t)(j0 + j) * bs_j];
-            Bs[kb][j] = u;
+            rb[h] = u;
         }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            int e = tid + h * 256;
+            int i, k;
+            if (a_kfast) { i = e / GK; k = e % GK; } else { k = e / NB; i = e % NB; }
+            As[k][i] = ra[h];
+            int j, kb;
+            if (b_jfast) { kb = e / NB; j = e % NB; } else { j = e / GK; kb = e % GK; }
+            Bs[kb][j] = rb[h];
+        }
+    };
+    if (kbeg < K) fetch(kbeg);
+    for (int k0 = kbeg; k0 < K; k0 += GK) {
+        stash();
         __syncthreads();
+        if (k0 + GK < K) fetch(k0 + GK);
         // v_mfma_f64_16x16x4: lane l supplies a(i = l % 16, k = l / 16) and b(k = l / 16, j = l % 16)
         const int kl = lane >> 4, il = lane & 15;
 #pragma unroll
