@@ -23,13 +23,25 @@ constexpr int LDT = BM + 4;   // padded LDS row
 __host__ __device__ inline int tiles_of(int d) { return (d + BM - 1) / BM; }
 
 // How many slices of the sample axis, and how long each is (multiple of BK), for a launch of
-// `ntri` output tiles.
-inline void split_plan_tiles(int64_t ntri, int64_t N, int *S, int64_t *kchunk)
+// `ntri` output tiles of `tile_elems` results each.  Workgroups are dealt evenly to the 256 CUs,
+// which work on several at a time, so the launch lasts as long as the CU with the most
+// workgroups: ceil(ntri S / 256) of them, each 1 / S of a tile's contraction.  More slices even
+// that out but cost S partial results written and read back; the plan minimises the sum of both
+// (matrix-core time at ~120 TFLOP/s, partial traffic at ~4 TB/s).
+inline void split_plan_tiles(int64_t ntri, int64_t N, int *S, int64_t *kchunk, double tile_elems = (double)BM * BM)
 {
-    int64_t s = (1024 + ntri - 1) / ntri;
-    int64_t smax = (N + 2047) / 2048;
-    if (s > smax) s = smax;
-    if (s < 1) s = 1;
+    const int64_t smax = (N + 2047) / 2048 > 0 ? (N + 2047) / 2048 : 1;
+    const double flops_tile = 2.0 * tile_elems * (double)N;
+    const double cu_rate = 120e12 / 256.0;
+    double best = 0.0;
+    int64_t s = 1;
+    for (int64_t c = 1; c <= smax && c <= 64; ++c) {
+        double per_cu = (double)((ntri * c + 255) / 256);   // workgroups on the busiest CU
+        if (per_cu < 4.0) per_cu = 4.0;                     // fewer than ~4 resident do not go faster
+        const double cost = per_cu * (flops_tile / (double)c) / cu_rate
+                            + (double)c * (double)ntri * tile_elems * 8.0 / 4e12;
+        if (c == 1 || cost < best) { best = cost; s = c; }
+    }
     int64_t kc = (N + s - 1) / s;
     kc = (kc + BK - 1) / BK * BK;
     if (kc < BK) kc = BK;
