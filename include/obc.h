@@ -139,9 +139,9 @@ int obc_prune_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d
  *                w_P^T ((H^-1)_P)^-1 w_P / 2
  *   trace        nullable, R x k_blocks x d out: the row after every block step
  * The traces feed obc_global_select (with d := k_blocks) and obc_gather_trace unchanged.
- * Workspace: obc_blocks_workspace_bytes.  strategy: OBC_STRATEGY_BLOCKED handles c = 4 only
- * (OBC_ERR_BAD_ARG otherwise); OBC_STRATEGY_AUTO uses it for c = 4 and the rank-1 solver for
- * every other block size. */
+ * Workspace: obc_blocks_workspace_bytes.  strategy: OBC_STRATEGY_BLOCKED handles c = 4 (and
+ * c = 1, which is obc_prune_rows) and returns OBC_ERR_BAD_ARG otherwise; OBC_STRATEGY_AUTO uses
+ * it for those and the rank-1 solver for every other block size. */
 int obc_blocks_workspace_bytes(int R, int d, int c, int strategy, size_t *bytes);
 int obc_prune_blocks(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d, int c, int k_blocks,
                      const int32_t *stop_counts, int32_t *order, float *loss, float *W_out, float *trace,

@@ -31,6 +31,7 @@ int pick_strategy(int strategy, int d)
 // Block pruning: the deferred-update solver handles blocks of 4; -1 when it is asked for others.
 int pick_block_strategy(int strategy, int d, int c)
 {
+    if (c == 1) return pick_strategy(strategy, d);
     if (strategy == OBC_STRATEGY_BLOCKED) return (c == 4 && d <= blocked_max_d()) ? OBC_STRATEGY_BLOCKED : -1;
     if (strategy == OBC_STRATEGY_RANK1 || c != 4) return OBC_STRATEGY_RANK1;
     return pick_strategy(OBC_STRATEGY_AUTO, d);
@@ -146,6 +147,9 @@ int obc_prune_blocks(obc_ctx *ctx, const float *W, const float *Hinv, int R, int
         return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_prune_blocks: null W, Hinv, order, loss or W_out");
     if (strategy < OBC_STRATEGY_AUTO || strategy > OBC_STRATEGY_BLOCKED)
         return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_prune_blocks: unknown strategy %d", strategy);
+    if (c == 1)   // blocks of one weight: Algorithm 1 itself
+        return obc_prune_rows(ctx, W, Hinv, R, d, k_blocks, 0, 0, stop_counts, nullptr, order, loss, W_out, trace,
+                              strategy, ws, ws_bytes);
     const int s = pick_block_strategy(strategy, d, c);
     if (s < 0)
         return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_prune_blocks: the deferred-update solver handles blocks of 4 only");
