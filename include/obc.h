@@ -16,7 +16,9 @@
  *    The library allocates no large memory: scratch is a caller-provided workspace whose
  *    size comes from the matching *_workspace_bytes query (host call, no GPU work).
  *  - All work is enqueued on the HIP stream given to obc_create and is asynchronous with
- *    respect to the host, except obc_invert and obc_check, which wait for the stream.
+ *    respect to the host, except obc_invert, obc_refit and obc_check, which wait for the stream,
+ *    and obc_prune_rows / obc_quant_rows when given a live mask, which wait once at their start
+ *    (the smallest number of already-pruned weights over the rows is read back).
  *  - Every call returns 0 (OBC_OK) or a negative OBC_ERR_* code; nothing throws or aborts
  *    across this boundary.  obc_last_error gives a text for the last failure on a context.
  *    Conditions only a kernel can see (a non-positive or non-finite pivot [H^-1]_pp) are

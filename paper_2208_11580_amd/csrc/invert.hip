@@ -62,9 +62,15 @@ __device__ __forceinline__ double rsqrt_f64(double x)
 // (v_mfma_f64_16x16x4: lane l supplies a(i = l % 16, k = l / 16) and b(k = l / 16, j = l % 16)
 // and holds c(4 r + l / 16, l % 16) in accumulator register r).  The off-diagonal sub-blocks of
 // L^-1 then follow from  T_is = -T_ii sum_{s <= k < i} L_ik T_ks.
+//
+// Batched use (one block per matrix): block b works on A + b strideA and Linv + b strideL; err is
+// the code latched on a bad pivot.
 __global__ __launch_bounds__(64) void potrf_wave_kernel(double *__restrict__ A, int lda, int bs,
-                                                        double *__restrict__ Linv, int *status)
+                                                        double *__restrict__ Linv, int *status,
+                                                        int64_t strideA, int64_t strideL, int err)
 {
+    A += (int64_t)blockIdx.x * strideA;
+    Linv += (int64_t)blockIdx.x * strideL;
     constexpr int PL = NB + 1;
     constexpr int SB = 16;                    // sub-block edge
     __shared__ double Ls[NB * PL];            // the block; becomes L (lower triangle)
@@ -202,7 +208,7 @@ __global__ __launch_bounds__(64) void potrf_wave_kernel(double *__restrict__ A, 
         if (i < bs && lane <= i) A[(int64_t)i * lda + lane] = Ls[i * PL + lane];
         Linv[i * NB + lane] = (lane <= i) ? Ts[i * PL + lane] : 0.0;
     }
-    if (lane == 0 && bad) obc_latch(status, OBC_ERR_NOT_SPD);
+    if (lane == 0 && bad) obc_latch(status, err);
 }
 
 // C (M x N, leading dimension ldc) = alpha * sum_k a(i,k) b(k,j) + beta * C, with
@@ -415,7 +421,7 @@ int factor_inverse(obc_ctx *ctx, const float *H, int d, void *ws, double **Yout)
         double *Akk = A + (int64_t)k0 * d + k0;
         double *Lk = Lb + (int64_t)kb * NB * NB;
         double *Yk = Y + (int64_t)k0 * d;
-        potrf_wave_kernel<<<1, 64, 0, st>>>(Akk, d, bs, Lk, ctx->d_status);
+        potrf_wave_kernel<<<1, 64, 0, st>>>(Akk, d, bs, Lk, ctx->d_status, 0, 0, OBC_ERR_NOT_SPD);
         // each workgroup overwrites exactly the rows / columns it has read
         GemmArgs trsm_row = mk(bs, nc, bs, 1.0, Lk, NB, 1, Yk, d, 1, 0.0, Yk, d, 0, 0, nullptr);
         if (m > 0) {
@@ -444,6 +450,22 @@ int inverse_from_factor(obc_ctx *ctx, const double *Y, int d, float *H)
 }
 
 }  // namespace
+
+namespace obc_rows {
+
+// R independent 64 x 64 symmetric positive definite matrices M (row-major, lower triangle used,
+// R x 4096 doubles) -> their Cholesky factors in place and the inverses of the factors in T
+// (R x 4096 doubles, zeros above the diagonal).  A bad pivot latches OBC_ERR_NUMERIC.
+int potrf64_batched_launch(obc_ctx *ctx, double *M, double *T, int R)
+{
+    if (R <= 0) return OBC_OK;
+    potrf_wave_kernel<<<R, 64, 0, ctx->stream>>>(M, NB, NB, T, ctx->d_status, (int64_t)NB * NB, (int64_t)NB * NB,
+                                                 OBC_ERR_NUMERIC);
+    OBC_LAUNCH_CHECK(ctx, "potrf_wave_kernel");
+    return OBC_OK;
+}
+
+}  // namespace obc_rows
 
 extern "C" {
 

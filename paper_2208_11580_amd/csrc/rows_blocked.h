@@ -41,6 +41,11 @@ struct BlockedWs {
     int *ndead;         // R   up-front eliminations
     int *nb;            // R   steps done in the last panel
     uint8_t *blk;       // R x d  N:M counters (d / M used)
+    // bulk elimination of already-pruned indices, BMAX at a time (rows_blocked.hip)
+    float *G;           // R x BMAX x ldu  rows of the matrix at the block's pivots
+    double *Mb;         // R x BMAX x BMAX the pivots' principal submatrix, then its Cholesky factor
+    double *Tb;         // R x BMAX x BMAX inverse of that factor
+    int *scal;          // [0] smallest number of up-front eliminations over the rows
 };
 
 

@@ -58,7 +58,12 @@ size_t carve(BlockedWs *ws, void *base, int R, int d)
     char *s2 = take((size_t)R * sizeof(int)), *s3 = take((size_t)R * sizeof(int));
     char *s4 = take((size_t)R * sizeof(int));
     char *pb = take((size_t)R * d);
+    char *pg = take((size_t)R * BMAX * ldu * sizeof(float));
+    char *pmb = take((size_t)R * BMAX * BMAX * sizeof(double));
+    char *ptb = take((size_t)R * BMAX * BMAX * sizeof(double));
+    char *psc = take(256);
     if (ws) {
+        ws->G = (float *)pg; ws->Mb = (double *)pmb; ws->Tb = (double *)ptb; ws->scal = (int *)psc;
         ws->Abuf[0] = (float *)p0; ws->Abuf[1] = (float *)p1; ws->U = (float *)pu; ws->ldu = ldu;
         ws->invd = (float *)pi; ws->piv = (int *)pp; ws->map = (int *)pm; ws->w = (double *)pw;
         ws->diag = (double *)pd; ws->orig = (int *)po; ws->m = (int *)s0; ws->done = (int *)s1;
@@ -120,6 +125,171 @@ __global__ __launch_bounds__(256) void blocked_init_kernel(InitArgs a)
 __global__ __launch_bounds__(256) void fill_f32_kernel(float *p, size_t n, float v)
 {
     for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n; e += (size_t)gridDim.x * 256) p[e] = v;
+}
+
+// ------------------------------------------------------------ bulk elimination of pruned indices
+// Already-pruned indices (quantization or pruning of the survivors of an earlier pass) leave the
+// inverse without any choice to make: they go in index order and change no weight.  For a set P of
+// BMAX of them the eliminations collapse into one block step (the block form of Lemma 1, as in
+// eq. (5)):  A <- A - A[:,P] (A[P,P])^-1 A[P,:] = A - U U^T  with  U = A[:,P] L^-T,  A[P,P] = L L^T.
+// That needs no vectors kept on chip, so the rank of the update is BMAX whatever the width of the
+// row -- the greedy panel manages 24 at 4608 -- and the flush that follows moves that much less.
+// Three kernels per block: gather A[:,P] and A[P,P]; factor A[P,P] and invert the factor (fp64,
+// one wavefront per row); U = L^-1 A[P,:] with the diagonal update and the compaction.  Every row
+// does the same number of such blocks (the smallest count of pruned indices over the rows decides);
+// what is left goes through the panel as before.
+struct DeadArgs {
+    const float *A_cur;
+    size_t a_row_stride;
+    int ld, swz, d;
+    BlockedWs ws;
+};
+
+__global__ __launch_bounds__(256) void min_ndead_kernel(const int *__restrict__ ndead, int R, int *out)
+{
+    __shared__ int red[256];
+    int v = 0x7fffffff;
+    for (int i = threadIdx.x; i < R; i += 256) v = ndead[i] < v ? ndead[i] : v;
+    red[threadIdx.x] = v;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] = red[threadIdx.x + w] < red[threadIdx.x] ? red[threadIdx.x + w] : red[threadIdx.x];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[0] = red[0];
+}
+
+// The block's pivots (the first BMAX pruned indices in compact order), the rows of the matrix at
+// them (G, in the old compact order) and their principal submatrix (Mb, fp64).
+__global__ __launch_bounds__(512) void dead_gather_kernel(DeadArgs a)
+{
+    __shared__ int pv[BMAX];
+    __shared__ int wcnt[8];
+    const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = a.ws.m[row];
+    const int *orig = a.ws.orig + (size_t)row * a.d;
+    int found = 0;                                       // pivots found so far (uniform)
+    for (int c0 = 0; c0 < m && found < BMAX; c0 += 512) {
+        const int j = c0 + tid;
+        const bool dead = j < m && orig[j] < 0;
+        const unsigned long long bal = __ballot(dead);
+        if (lane == 0) wcnt[wave] = __popcll(bal);
+        __syncthreads();
+        int before = found, total = 0;
+        for (int w = 0; w < 8; ++w) {
+            if (w < wave) before += wcnt[w];
+            total += wcnt[w];
+        }
+        const int rank = before + __popcll(bal & ((1ull << lane) - 1ull));
+        if (dead && rank < BMAX) pv[rank] = j;
+        found += total;
+        __syncthreads();
+    }
+    // (the host only launches this while every row still has BMAX pruned indices)
+    const float *Acur = a.A_cur + (size_t)row * a.a_row_stride;
+    float *G = a.ws.G + (size_t)row * BMAX * a.ws.ldu;
+    for (int r = 0; r < BMAX; ++r) {
+        const int p = pv[r];
+        for (int j = tid; j < m; j += 512) {
+            const int hi = (j <= p) ? p : j, lo = (j <= p) ? j : p;
+            const size_t off = a.swz ? quad_index(hi, lo, a.ld) : (size_t)hi * a.ld + lo;
+            G[(size_t)r * a.ws.ldu + j] = Acur[off];
+        }
+    }
+    if (tid < BMAX) a.ws.piv[(size_t)row * BMAX + tid] = pv[tid];
+    __syncthreads();                                     // G visible to the whole workgroup
+    double *Mb = a.ws.Mb + (size_t)row * BMAX * BMAX;
+    for (int e = tid; e < BMAX * BMAX; e += 512) {
+        const int r = e / BMAX, s2 = e % BMAX;
+        Mb[e] = (double)G[(size_t)r * a.ws.ldu + pv[s2]];
+    }
+}
+
+// U = T G (T = L^-1 lower triangular, fp32 here), written in the new compact order; the diagonal
+// loses sum_k U[k][j]^2; weights, diagonal, original indices and the index map are compacted.
+// Only the owner of column j ever touches G[:, j], so once it has read the column it parks the
+// column's new diagonal entry and new index there (rows 0..2) until the compaction.
+__global__ __launch_bounds__(512) void dead_apply_kernel(DeadArgs a)
+{
+    __shared__ __align__(16) float Tl[BMAX][BMAX];       // T[k][r]
+    __shared__ int pv[BMAX];
+    const int row = blockIdx.x, tid = threadIdx.x, d = a.d;
+    const int m = a.ws.m[row];
+    const int ldu = a.ws.ldu;
+    const double *Tb = a.ws.Tb + (size_t)row * BMAX * BMAX;
+    for (int e = tid; e < BMAX * BMAX; e += 512) Tl[e / BMAX][e % BMAX] = (float)Tb[e];
+    if (tid < BMAX) pv[tid] = a.ws.piv[(size_t)row * BMAX + tid];
+    __syncthreads();
+    float *G = a.ws.G + (size_t)row * BMAX * ldu;
+    float *U = a.ws.U + (size_t)row * BMAX * ldu;
+    double *gw = a.ws.w + (size_t)row * d;
+    double *gd = a.ws.diag + (size_t)row * d;
+    int *go = a.ws.orig + (size_t)row * d;
+    int *gmap = a.ws.map + (size_t)row * d;
+
+#pragma unroll 1
+    for (int j = tid; j < m; j += 512) {
+        int below = 0;
+        bool piv = false;
+        for (int s2 = 0; s2 < BMAX; ++s2) {
+            below += (pv[s2] < j) ? 1 : 0;
+            piv = piv || (pv[s2] == j);
+        }
+        int jnew = -1;
+        double newd = 0.0;
+        if (!piv) {
+            jnew = j - below;
+            float g[BMAX];
+#pragma unroll
+            for (int r = 0; r < BMAX; ++r) g[r] = G[(size_t)r * ldu + j];
+            double dsum = 0.0;
+#pragma unroll
+            for (int k = 0; k < BMAX; ++k) {
+                float acc = 0.f;
+#pragma unroll
+                for (int r = 0; r <= k; ++r) acc = fmaf(Tl[k][r], g[r], acc);
+                U[(size_t)k * ldu + jnew] = acc;
+                dsum += (double)acc * (double)acc;
+                // one row of T at a time (otherwise its LDS reads are all issued up front)
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            newd = gd[j] - dsum;
+        }
+        const long long bits = __double_as_longlong(newd);
+        G[j] = __int_as_float((int)(unsigned)bits);
+        G[(size_t)ldu + j] = __int_as_float((int)(unsigned)((unsigned long long)bits >> 32));
+        G[(size_t)2 * ldu + j] = __int_as_float(jnew);
+    }
+    // compaction: read the old entries, wait for everybody, write the new ones
+    constexpr int EMAX = 10;                             // ceil(largest d / 512)
+    double wv[EMAX], dv[EMAX];
+    int ov[EMAX], jn[EMAX];
+#pragma unroll
+    for (int e = 0; e < EMAX; ++e) {
+        const int j = tid + e * 512;
+        jn[e] = -1;
+        if (j >= m) continue;
+        jn[e] = __float_as_int(G[(size_t)2 * ldu + j]);
+        const unsigned lo = (unsigned)__float_as_int(G[j]), hi = (unsigned)__float_as_int(G[(size_t)ldu + j]);
+        dv[e] = __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+        wv[e] = gw[j];
+        ov[e] = go[j];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < EMAX; ++e) {
+        if (jn[e] < 0) continue;
+        gw[jn[e]] = wv[e];
+        gd[jn[e]] = dv[e];
+        go[jn[e]] = ov[e];
+        gmap[jn[e]] = tid + e * 512;
+    }
+    if (tid < BMAX) a.ws.invd[(size_t)row * BMAX + tid] = 1.f;
+    if (tid == 0) {
+        a.ws.m[row] = m - BMAX;
+        a.ws.done[row] += BMAX;
+        a.ws.nb[row] = BMAX;
+    }
 }
 
 // ----------------------------------------------------------------------------------------- flush
@@ -378,6 +548,8 @@ int blocked_max_d() { return kVariants[kNumVariants - 1].cap; }
 
 size_t blocked_workspace_bytes(int R, int d) { return carve(nullptr, nullptr, R, d); }
 
+int potrf64_batched_launch(obc_ctx *ctx, double *M, double *T, int R);   // invert.hip
+
 int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, int R, int d, int k_steps,
                    int nm_n, int nm_m, const int32_t *stop_counts, const float *delta,
                    const float *offset, int maxq, const uint8_t *live, int flags, int32_t *order, float *loss,
@@ -417,13 +589,88 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
     int host_done = 0;
     int cur = -1;            // -1: the shared H^-1; otherwise index into Abuf
     int ld_cur = d;
+
+    // where the rows' matrices are now, as the kernels take it
+    auto cur_matrix = [&](const float **A, size_t *stride, int *swz) {
+        *A = (cur < 0) ? Hinv : bw.Abuf[cur];
+        *stride = (cur < 0) ? 0 : mat_stride;
+        *swz = (cur < 0) ? 0 : 1;
+    };
+    // rank-K update and compaction of every row's matrix into the other buffer
+    auto launch_flush = [&](int K) -> int {
+        const int m_next = d - host_done;
+        const int nxt = (cur < 0) ? 0 : 1 - cur;
+        int swz;
+        cur_matrix(&fa.A_old, &fa.old_row_stride, &swz);
+        fa.ld_old = ld_cur;
+        fa.old_swz = swz;
+        fa.A_new = bw.Abuf[nxt];
+        fa.new_row_stride = mat_stride;
+        fa.ld_new = m_next;
+        // strips of 256 rows where two workgroups' tiles fit in a CU's LDS, else 128
+        const int halves = (K <= 48) ? 2 : 1;
+        fa.strips = (m_next + halves * FT - 1) / (halves * FT);
+        const int rows8 = (R + 7) / 8 * 8;
+        {
+            // one triangle of the surviving m_next x m_next part of every row's inverse is read and
+            // written once
+            const double tri = 0.5 * (double)m_next * (m_next + 1.0);   // entries of one triangle
+            obc_scope sc(ctx, OBC_KERNEL_FLUSH, (double)R * 8.0 * tri, (double)R * 2.0 * K * tri);
+            const dim3 grid(fa.strips * rows8);
+            switch (K) {
+            case 24: flush_kernel<24, 2><<<grid, 512, 0, st>>>(fa); break;
+            case 36: flush_kernel<36, 2><<<grid, 512, 0, st>>>(fa); break;
+            case 48: flush_kernel<48, 2><<<grid, 512, 0, st>>>(fa); break;
+            case 56: flush_kernel<56, 1><<<grid, 512, 0, st>>>(fa); break;
+            case 64: flush_kernel<64, 1><<<grid, 512, 0, st>>>(fa); break;
+            default: return obc_fail(ctx, OBC_ERR_BAD_ARG, "row solver: no flush kernel for block size %d", K);
+            }
+        }
+        OBC_LAUNCH_CHECK(ctx, "flush_kernel");
+        cur = nxt;
+        ld_cur = fa.ld_new;
+        return OBC_OK;
+    };
+
+    // ---- already-pruned indices, BMAX at a time, as long as every row has that many left.  The
+    // smallest count over the rows is read back once (the only wait in this call).
+    if (live && mode != MODE_BLOCK) {
+        int min_dead = 0;
+        min_ndead_kernel<<<1, 256, 0, st>>>(bw.ndead, R, bw.scal);
+        OBC_LAUNCH_CHECK(ctx, "min_ndead_kernel");
+        OBC_HIP(ctx, hipMemcpyAsync(&min_dead, bw.scal, sizeof(int), hipMemcpyDeviceToHost, st));
+        OBC_HIP(ctx, hipStreamSynchronize(st));
+        int nfast = min_dead / BMAX;
+        if (d - nfast * BMAX < BMAX) nfast -= 1;            // keep a matrix for the flush to write
+        DeadArgs da;
+        da.d = d; da.ws = bw;
+        for (int it = 0; it < nfast; ++it) {
+            const int m_max = d - host_done;
+            cur_matrix(&da.A_cur, &da.a_row_stride, &da.swz);
+            da.ld = ld_cur;
+            {
+                obc_scope sc(ctx, OBC_KERNEL_PANEL, (double)R * BMAX * 4.0 * m_max,
+                             (double)R * BMAX * (double)BMAX * m_max);
+                dead_gather_kernel<<<R, 512, 0, st>>>(da);
+                OBC_LAUNCH_CHECK(ctx, "dead_gather_kernel");
+                int rc = potrf64_batched_launch(ctx, bw.Mb, bw.Tb, R);
+                if (rc != OBC_OK) return rc;
+                dead_apply_kernel<<<R, 512, 0, st>>>(da);
+                OBC_LAUNCH_CHECK(ctx, "dead_apply_kernel");
+            }
+            host_done += BMAX;
+            int rc = launch_flush(BMAX);
+            if (rc != OBC_OK) return rc;
+        }
+    }
+
     while (host_done < host_total) {
         const int m_max = d - host_done;
         const Variant *v = pick_variant(m_max, R);
-        pa.A_cur = (cur < 0) ? Hinv : bw.Abuf[cur];
-        pa.a_row_stride = (cur < 0) ? 0 : mat_stride;
+        int swz;
+        cur_matrix(&pa.A_cur, &pa.a_row_stride, &swz);
         pa.ld = ld_cur;
-        pa.swz = (cur < 0) ? 0 : 1;
+        pa.swz = swz;
         {
             // a panel reads one (corrected) matrix row per step: 4 m bytes, and does ~B m flops on it
             const int steps = (host_total - host_done < v->B) ? host_total - host_done : v->B;
@@ -435,37 +682,8 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
         OBC_LAUNCH_CHECK(ctx, "panel_kernel");
         host_done += v->B;
         if (host_done >= host_total) break;
-        const int m_next = d - host_done;
-        const int nxt = (cur < 0) ? 0 : 1 - cur;
-        fa.A_old = pa.A_cur;
-        fa.old_row_stride = pa.a_row_stride;
-        fa.ld_old = ld_cur;
-        fa.old_swz = pa.swz;
-        fa.A_new = bw.Abuf[nxt];
-        fa.new_row_stride = mat_stride;
-        fa.ld_new = m_next;
-        // rows per strip, in 128-row halves: as tall as two workgroups' F tiles allow in a CU's LDS
-        const int halves = (v->B <= 48) ? 2 : 1;
-        fa.strips = (m_next + halves * FT - 1) / (halves * FT);
-        const int rows8 = (R + 7) / 8 * 8;
-        {
-            // one triangle of the surviving m_next x m_next part of every row's inverse is read and
-            // written once
-            const double tri = 0.5 * (double)m_next * (m_next + 1.0);   // entries of one triangle
-            obc_scope sc(ctx, OBC_KERNEL_FLUSH, (double)R * 8.0 * tri, (double)R * 2.0 * v->B * tri);
-            const dim3 grid(fa.strips * rows8);
-            switch (v->B) {
-            case 24: flush_kernel<24, 2><<<grid, 512, 0, st>>>(fa); break;
-            case 36: flush_kernel<36, 2><<<grid, 512, 0, st>>>(fa); break;
-            case 48: flush_kernel<48, 2><<<grid, 512, 0, st>>>(fa); break;
-            case 56: flush_kernel<56, 1><<<grid, 512, 0, st>>>(fa); break;
-            case 64: flush_kernel<64, 1><<<grid, 512, 0, st>>>(fa); break;
-            default: return obc_fail(ctx, OBC_ERR_BAD_ARG, "row solver: no flush kernel for block size %d", v->B);
-            }
-        }
-        OBC_LAUNCH_CHECK(ctx, "flush_kernel");
-        cur = nxt;
-        ld_cur = fa.ld_new;
+        int rc = launch_flush(v->B);
+        if (rc != OBC_OK) return rc;
     }
     return OBC_OK;
 }
