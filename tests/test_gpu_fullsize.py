@@ -276,3 +276,29 @@ def test_width_4608_first_blocks(obc, orc):
     dW = (W - q["W"]).double()
     quad = 0.5 * ((dW @ H) * dW).sum(dim=1)
     assert torch.allclose(q["loss"].double().sum(dim=1), quad, rtol=5e-3)
+
+
+def test_width_4608_quantize_survivors(obc, orc):
+    """Prune-then-quantize at d_col = 4608: half of every row is pruned, the survivors are quantized
+    on the dense sub-problem.  The GPU removes the pruned indices from H^-1 in blocks of 64 (block
+    form of Lemma 1) and the rest one by one; the oracle inverts the survivors' sub-Hessian."""
+    W, X, _ = obc_inputs.make_layer("conv512x4608", device="cuda", d_row=3, n_samples=12000)
+    R, d = W.shape
+    Hinv = obc.obc_invert(obc.obc_hessian(X))
+    counts = torch.tensor([d // 2, d // 2 - 37, d // 2 + 101], dtype=torch.int32, device="cuda")
+    p = obc.obc_prune_rows(W, Hinv, k_steps=d // 2 + 101, stop_counts=counts)
+    live = (p["W"] != 0).to(torch.uint8)
+    assert torch.equal((1 - live).sum(dim=1).to(torch.int32), counts)
+    delta, offset, maxq = obc.obc_minmax_grid(p["W"], 4, live=live)
+    q = obc.obc_quant_rows(p["W"], Hinv, delta, offset, maxq, live=live)
+    obc.obc_check()
+    i = 1
+    st = RowParity()
+    k = int(live[i].sum())
+    check_row(orc, st, "quant", _np(Hinv), _np(p["W"][i]), _np(q["order"][i]), _np(q["loss"][i]), _np(q["W"][i]), k,
+              grid=(float(delta[i]), float(offset[i]), maxq), g_codes=_np(q["codes"][i]), live=_np(live[i]))
+    print(st)
+    # every row: pruned weights stay zero with code -1, survivors sit on their grid
+    assert torch.all(q["W"][live == 0] == 0) and torch.all(q["codes"][live == 0] == -1)
+    c = q["codes"]
+    assert int(c[live != 0].min()) >= 0 and int(c[live != 0].max()) <= maxq
