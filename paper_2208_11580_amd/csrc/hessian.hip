@@ -177,19 +177,42 @@ __global__ __launch_bounds__(256) void nt_partial_kernel(const float *__restrict
             }
 }
 
-// H[i][j] (+)= 2 * sum_s partial[s][min-tile-order(i, j)], slices added in index order.
+// H (+)= 2 * sum_s partial[s] on the tiles on or above the block diagonal, slices added in index
+// order, and the mirror image below it.  One workgroup per 32 x 32 piece of such a tile: the sums
+// are read and written along rows, the mirrored piece goes through LDS so that it is written
+// along rows too.
 __global__ __launch_bounds__(256) void syrk_reduce_kernel(const float *__restrict__ partial, int S,
                                                           int d, int accumulate,
                                                           float *__restrict__ H)
 {
-    int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= (int64_t)d * d) return;
-    int i = (int)(e / d), j = (int)(e % d);
-    int64_t src = (i / BM <= j / BM) ? (int64_t)i * d + j : (int64_t)j * d + i;
-    float s = 0.f;
-    for (int k = 0; k < S; ++k) s += partial[(int64_t)k * d * d + src];
-    s *= 2.f;
-    H[e] = accumulate ? H[e] + s : s;
+    __shared__ float Tt[32][33];
+    const int pi = blockIdx.y, pj = blockIdx.x;           // 32 x 32 piece (pi, pj)
+    if (pi / (BM / 32) > pj / (BM / 32)) return;          // its 128-tile lies below the block diagonal
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const bool mirror = (pi / (BM / 32) != pj / (BM / 32));
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int i = pi * 32 + ty + 8 * r, j = pj * 32 + tx;
+        float s = 0.f;
+        if (i < d && j < d) {
+            const int64_t e = (int64_t)i * d + j;
+            for (int k = 0; k < S; ++k) s += partial[(int64_t)k * d * d + e];
+            s *= 2.f;
+            H[e] = accumulate ? H[e] + s : s;
+        }
+        Tt[ty + 8 * r][tx] = s;
+    }
+    if (!mirror) return;
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int i = pj * 32 + ty + 8 * r, j = pi * 32 + tx;   // (i, j) of the mirrored piece
+        if (i < d && j < d) {
+            const int64_t e = (int64_t)i * d + j;
+            const float s = Tt[tx][ty + 8 * r];
+            H[e] = accumulate ? H[e] + s : s;
+        }
+    }
 }
 
 // C[e] (+)= 2 * sum_s partial[s][e] over a dense da x db result, slices added in index order.
@@ -256,8 +279,8 @@ int obc_hessian(obc_ctx *ctx, const float *X, int d, int64_t N, int64_t ldx, flo
 
     nt_partial_kernel<true><<<dim3(ntri, S), 256, 0, ctx->stream>>>(X, d, ldx, X, d, ldx, N, kchunk, partial, vec_ok);
     OBC_LAUNCH_CHECK(ctx, "nt_partial_kernel");
-    const int64_t n = (int64_t)d * d;
-    syrk_reduce_kernel<<<(unsigned)((n + 255) / 256), 256, 0, ctx->stream>>>(partial, S, d, accumulate, H);
+    const unsigned np32 = (unsigned)((d + 31) / 32);
+    syrk_reduce_kernel<<<dim3(np32, np32), 256, 0, ctx->stream>>>(partial, S, d, accumulate, H);
     OBC_LAUNCH_CHECK(ctx, "syrk_reduce_kernel");
     if (damp_rel >= 0.f) {
         dampen_kernel<<<1, 1024, 0, ctx->stream>>>(H, d, damp_rel);
