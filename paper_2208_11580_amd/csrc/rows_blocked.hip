@@ -23,13 +23,16 @@
 //                 part of A0[p,:] (barrier 2), then the row is corrected, w / diag are updated and
 //                 u_s is kept (registers) and stored (HBM, for the flush).
 //   flush_kernel  A0_new = compact(A0 - U diag(1/a) U^T): 128x128 tiles on v_mfma_f32_32x32x2_f32,
-//                 one workgroup per 128-row strip of one row's matrix.  The eliminated rows and
-//                 columns are dropped while writing (out of place, two buffers), so the matrix
-//                 shrinks with the live set and later blocks cost (m/d)^2 of the first.
+//                 one workgroup per strip of 128 or 256 rows of one row's matrix (only the lower
+//                 triangle is kept).  The eliminated rows and columns are dropped while writing
+//                 (out of place, two buffers), so the matrix shrinks with the live set and later
+//                 blocks cost (m/d)^2 of the first.
 //
 // The first block reads the shared H^-1 directly, so no per-row copy of it is ever made.
-// Already-pruned weights (quantization of survivors) enter as candidates with score -1: they are
-// eliminated first, in index order, with no weight change and nothing recorded.
+// Already-pruned weights (quantization or pruning of survivors) are eliminated first, in index
+// order, with no weight change and nothing recorded: 64 at a time by a block form of Lemma 1 as
+// long as every row has that many left (see "bulk elimination" below), the rest as candidates
+// with score -infinity inside the panel.
 #include "rows_blocked.h"
 
 namespace {
