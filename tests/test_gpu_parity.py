@@ -608,3 +608,64 @@ def test_rows_many_more_rows_than_cus(obc, orc):
     srt = torch.sort(blk["order"], dim=1).values
     assert torch.equal(srt, torch.arange(kb, device="cuda", dtype=torch.int32).expand(R, kb))
     assert torch.all(blk["W"] == 0)
+
+
+def test_edge_cases_of_the_widened_entry_points(obc, orc):
+    """Smallest shapes and degenerate masks: one sample, one column, one block, rows whose weights are
+    all pruned already, every row with enough pruned weights for the bulk elimination."""
+    ctx = obc
+    torch.manual_seed(0)
+    for N in (1, 3, 17):
+        X = torch.randn(5, N, device="cuda")
+        Y = torch.randn(3, N, device="cuda")
+        C = ctx.obc_cross(X, Y)
+        assert np.allclose(_np(C), orc.cross(_np(X), _np(Y)), rtol=1e-5, atol=1e-6), N
+    X = torch.randn(1, 50, device="cuda")
+    Y = torch.randn(2, 50, device="cuda")
+    H = ctx.obc_hessian(X)
+    C = ctx.obc_cross(X, Y)
+    assert np.allclose(_np(ctx.obc_refit(H, C)), orc.refit(_np(H), _np(C)), rtol=1e-5)
+    # a row that is one block
+    X = torch.randn(4, 64, device="cuda")
+    W = torch.randn(3, 4, device="cuda")
+    Hinv = _hinv(ctx, X)
+    for st in (0, 1, 2):
+        r = ctx.obc_prune_blocks(W, Hinv, 4, strategy=st)
+        ctx.obc_check()
+        assert torch.all(r["W"] == 0) and torch.all(r["order"] == 0)
+        ro = orc.block_prune_row(_np(Hinv).astype(np.float64), _np(W[0]).astype(np.float64), 4)
+        assert abs(r["loss"][0, 0].item() - ro.loss[0]) <= 1e-4 * ro.loss[0]
+    # live masks on both solvers
+    d = 260
+    X = torch.randn(d, 1000, device="cuda")
+    W = torch.randn(3, d, device="cuda") * 0.1
+    Hinv = _hinv(ctx, X)
+    for st in (1, 2):
+        live = torch.ones(3, d, dtype=torch.uint8, device="cuda")
+        live[1] = 0                                  # a row with nothing left
+        Wl = W * live
+        delta, offset, maxq = ctx.obc_minmax_grid(Wl, 4, live=live)
+        q = ctx.obc_quant_rows(Wl, Hinv, delta, offset, maxq, live=live, strategy=st)
+        ctx.obc_check()
+        assert torch.all(q["W"][1] == 0) and torch.all(q["codes"][1] == -1)
+        q0 = ctx.obc_quant_rows(W, Hinv, *ctx.obc_minmax_grid(W, 4)[:2], 15, strategy=st)
+        assert torch.equal(q["W"][0], q0["W"][0]) and torch.equal(q["order"][2], q0["order"][2])
+        p = ctx.obc_prune_rows(Wl, Hinv, k_steps=10, live=live, strategy=st)
+        ctx.obc_check()
+        assert torch.all(p["W"][1] == 0) and torch.all(p["order"][1] == -1)
+        # every row has at least 64 pruned weights (bulk elimination), one row has no survivor
+        live2 = torch.ones(3, d, dtype=torch.uint8, device="cuda")
+        live2[:, :130] = 0
+        live2[2, :] = 0
+        W2 = W * live2
+        p2 = ctx.obc_prune_rows(W2, Hinv, k_steps=20, live=live2, strategy=st)
+        ctx.obc_check()
+        Hfull = np.linalg.inv(_np(Hinv).astype(np.float64))
+        ref = orc.prune_row(orc.invert(Hfull[130:, 130:]), _np(W2[0, 130:]).astype(np.float64), k_steps=20)
+        assert np.array_equal(_np(p2["order"][0]) - 130, ref.order)
+        assert np.allclose(_np(p2["W"][0, 130:]), ref.w, rtol=1e-3, atol=1e-6)
+        assert torch.all(p2["W"][2] == 0)
+    # the outlier flag with a single-point grid: everything is an outlier until it sits at zero
+    a = ctx.obc_quant_rows(W, Hinv, torch.ones(3, device="cuda"), torch.zeros(3, device="cuda"), 0, outliers=True)
+    ctx.obc_check()
+    assert torch.all(a["W"] == 0)
