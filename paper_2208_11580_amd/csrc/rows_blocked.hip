@@ -335,11 +335,21 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     __shared__ int rowoff_s[SR];   // byte offset of each strip row in the old matrix
     __shared__ int rowold_s[SR];   // its old compact index
 
-    // workgroups are dealt round-robin to the 8 XCDs: keep all strips of one row on one XCD so
-    // that its U panel and index map stay in that XCD's L2
+    // Workgroups are dealt round-robin to the 8 XCDs: all strips of one row stay on one XCD, so
+    // that its U panel and index map stay in that XCD's L2.  Within an XCD the rows go in groups
+    // of G, and a group's workgroups run strip-major (the longest strip of each of its rows, then
+    // the next longest, ...): long strips start first, and workgroups that start together take
+    // equally long.  Measured against one row's strips in a run (lengths in a sawtooth): 10 % less
+    // time per launch, 20 % where the strip count is a multiple of 4 (every fourth workgroup of
+    // an XCD then got the long strips); G = 4, 8, 16, 32 gave 21.0, 20.3, 19.8, 20.4 ms of flush
+    // time on the 256 x 2304 layer (22.2 ms before).
     const int L = blockIdx.x;
-    const int row = (L / (8 * a.strips)) * 8 + (L % 8);
-    const int strip = a.strips - 1 - (L / 8) % a.strips;   // longest strips first
+    const int nx = gridDim.x / (8 * a.strips);            // rows per XCD
+    constexpr int G = 16;
+    const int grp = (L / 8) / (G * a.strips), within = (L / 8) - grp * G * a.strips;
+    const int rig = nx - G * grp < G ? nx - G * grp : G;  // rows in this group
+    const int strip = a.strips - 1 - within / rig;
+    const int row = (G * grp + within % rig) * 8 + (L % 8);
     if (row >= a.R) return;
     if (a.ws.nb[row] != KMAX || a.ws.done[row] >= a.ws.total[row]) return;
     constexpr int nb = KMAX;
