@@ -248,7 +248,7 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
         int j = tid + e * T;
         const int hi = (j <= p) ? p : j, lo = (j <= p) ? j : p;
         size_t off = pr.swz ? quad_index(hi, lo, pr.ld) : (size_t)hi * pr.ld + lo;
-        col[e] = (j < pr.m) ? pr.Acur[off] : 0.f;
+        col[e] = (j < pr.m) ? __builtin_nontemporal_load(&pr.Acur[off]) : 0.f;
     }
     // the owner of p publishes the pivot's data, the step's scalars and the coefficients
     // u_r[p] / a_r of the earlier steps of this block
@@ -320,15 +320,17 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
     }
     const double g = sh.bc_g, invapp = sh.bc_invapp;
     const bool isdead = sh.bc_o < 0;
-    // coefficients of this step, once, into registers
+    // coefficients of this step, once, into scalar registers (they are the same for every lane;
+    // as vector registers they would take up to B of them next to the block vectors)
     float cv[S > 0 ? S : 1];
+    auto uni = [](float x) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(x))); };
 #pragma unroll
     for (int r4 = 0; r4 < S; r4 += 4) {
         float4 c4 = *reinterpret_cast<const float4 *>(&sh.cvec[r4]);
-        cv[r4] = c4.x;
-        if (r4 + 1 < S) cv[r4 + 1] = c4.y;
-        if (r4 + 2 < S) cv[r4 + 2] = c4.z;
-        if (r4 + 3 < S) cv[r4 + 3] = c4.w;
+        cv[r4] = uni(c4.x);
+        if (r4 + 1 < S) cv[r4 + 1] = uni(c4.y);
+        if (r4 + 2 < S) cv[r4 + 2] = uni(c4.z);
+        if (r4 + 3 < S) cv[r4 + 3] = uni(c4.w);
     }
 
     // ---- (3) bring the fetched row up to date, keep it, update w and the diagonal
