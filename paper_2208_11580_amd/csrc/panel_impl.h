@@ -12,10 +12,13 @@ namespace obc_blocked {
 #ifndef OBC_TICK_MIN_M
 #define OBC_TICK_MIN_M 0       // only launches with a live size above this are timed
 #endif
+#ifndef OBC_TICK_MAX_M
+#define OBC_TICK_MAX_M 0x7fffffff
+#endif
 extern __device__ unsigned long long obc_panel_timing[8];
 #define OBC_TICK(slot)                                                        \
     do {                                                                      \
-        if (blockIdx.x == 0 && threadIdx.x == 0 && pr.m > OBC_TICK_MIN_M) {   \
+        if (blockIdx.x == 0 && threadIdx.x == 0 && pr.m > OBC_TICK_MIN_M && pr.m <= OBC_TICK_MAX_M) { \
             unsigned long long now__ = __builtin_readcyclecounter();          \
             atomicAdd(&obc_panel_timing[slot], now__ - pr.tick);              \
             const_cast<PanelRow &>(pr).tick = now__;                          \
@@ -110,51 +113,40 @@ __device__ __forceinline__ double quad_block_score(double w, double dg, const fl
     return bad ? __builtin_nan("") : s;
 }
 
-// one DPP stage of a 64-bit unsigned minimum: combine with the lane `row_shr` positions down the
-// 16-lane row (lanes shifted in from outside the row contribute the identity)
+// One DPP stage of an unsigned minimum: combine with the lane `row_shr` positions down the
+// 16-lane row (lanes shifted in from outside the row contribute the identity).
 template <int CTRL>
-__device__ __forceinline__ unsigned long long dpp_min_stage(unsigned long long k)
+__device__ __forceinline__ unsigned dpp_umin_stage(unsigned v)
 {
-    unsigned lo = (unsigned)k, hi = (unsigned)(k >> 32);
-    unsigned olo = (unsigned)__builtin_amdgcn_update_dpp(-1, (int)lo, CTRL, 0xf, 0xf, false);
-    unsigned ohi = (unsigned)__builtin_amdgcn_update_dpp(-1, (int)hi, CTRL, 0xf, 0xf, false);
-    unsigned long long o = ((unsigned long long)ohi << 32) | olo;
-    return o < k ? o : k;
+    const unsigned o = (unsigned)__builtin_amdgcn_update_dpp(-1, (int)v, CTRL, 0xf, 0xf, false);
+    return o < v ? o : v;
 }
 
-// minimum over each 16-lane row, returned from the row's last lane of the caller's choice
-__device__ __forceinline__ unsigned long long row16_reduce(unsigned long long k)
+// minimum over each 16-lane row, valid in the row's last lane
+__device__ __forceinline__ unsigned row16_umin(unsigned v)
 {
-    k = dpp_min_stage<0x111>(k);   // row_shr:1
-    k = dpp_min_stage<0x112>(k);   // row_shr:2
-    k = dpp_min_stage<0x114>(k);   // row_shr:4
-    k = dpp_min_stage<0x118>(k);   // row_shr:8
-    return k;                      // lane 15 of every row holds the row's minimum
-}
-
-__device__ __forceinline__ unsigned long long read_lane_key(unsigned long long k, int l)
-{
-    unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)k, l);
-    unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(k >> 32), l);
-    return ((unsigned long long)hi << 32) | lo;
+    v = dpp_umin_stage<0x111>(v);   // row_shr:1
+    v = dpp_umin_stage<0x112>(v);   // row_shr:2
+    v = dpp_umin_stage<0x114>(v);   // row_shr:4
+    v = dpp_umin_stage<0x118>(v);   // row_shr:8
+    return v;
 }
 
 // minimum over the wavefront (uniform result)
-__device__ __forceinline__ unsigned long long wave_min_key(unsigned long long k)
+__device__ __forceinline__ unsigned wave_umin(unsigned v)
 {
-    k = row16_reduce(k);
-    unsigned long long a0 = read_lane_key(k, 15), a1 = read_lane_key(k, 31);
-    unsigned long long a2 = read_lane_key(k, 47), a3 = read_lane_key(k, 63);
+    v = row16_umin(v);
+    unsigned a0 = (unsigned)__builtin_amdgcn_readlane((int)v, 15), a1 = (unsigned)__builtin_amdgcn_readlane((int)v, 31);
+    unsigned a2 = (unsigned)__builtin_amdgcn_readlane((int)v, 47), a3 = (unsigned)__builtin_amdgcn_readlane((int)v, 63);
     a0 = a1 < a0 ? a1 : a0;
     a2 = a3 < a2 ? a3 : a2;
     return a2 < a0 ? a2 : a0;
 }
 
 // minimum over the first 16 lanes' values (every row holds the same 16 values; uniform result)
-__device__ __forceinline__ unsigned long long row16_min_key(unsigned long long k)
+__device__ __forceinline__ unsigned row16_umin_all(unsigned v)
 {
-    k = row16_reduce(k);
-    return read_lane_key(k, 15);
+    return (unsigned)__builtin_amdgcn_readlane((int)row16_umin(v), 15);
 }
 
 struct PanelRow {
@@ -181,9 +173,10 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
     // ---- (1) selection.  The error (target - w) is formed in fp64 (for OBQ it is a difference of
     // nearby numbers); the score itself, error^2 / a_jj, is only compared, so it is taken in fp32
     // with the hardware reciprocal (2 ulp): candidates closer than that count as tied.
-    // A candidate is the 64-bit key (order-preserving bits of the score, index): the unsigned
-    // minimum of the keys is the argmin with ties to the lowest index.
-    unsigned long long key = ~0ull;
+    // A candidate is the pair (order-preserving bits of the score, index); the argmin with ties to
+    // the lowest index is taken in two unsigned 32-bit minima: the least score, then the least
+    // index among the candidates that have it.  All ones = no candidate.
+    unsigned cs = ~0u, ci = ~0u;
     if constexpr (MODE == MODE_BLOCK) {
         // a block is chosen every fourth step; the three steps after it take its other weights
         if constexpr (S % 4 == 0) {
@@ -191,8 +184,8 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
             for (int e = 0; e < EPT; ++e) {
                 const float sc = (float)quad_block_score(st.w[e], st.dg[e], st.ob[e]);
                 if (st.alive[e] && sc == sc) {
-                    unsigned long long k = ((unsigned long long)score_bits(sc) << 32) | (unsigned)((tid & ~3) + e * T);
-                    key = k < key ? k : key;
+                    const unsigned b = score_bits(sc);
+                    if (b < cs) { cs = b; ci = (unsigned)((tid & ~3) + e * T); }   // (indices ascend with e)
                 }
             }
         }
@@ -218,8 +211,8 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
             if (MODE == MODE_QUANT && a.outliers && fabs(er) > 0.5 * pr.qd) sc = outlier_first(sc);
         }
         if (sc == sc) {   // a NaN score is no candidate
-            unsigned long long k = ((unsigned long long)score_bits(sc) << 32) | (unsigned)(tid + e * T);
-            key = k < key ? k : key;
+            const unsigned b = score_bits(sc);
+            if (b < cs) { cs = b; ci = (unsigned)(tid + e * T); }   // (indices ascend with e)
         }
     }
     }
@@ -228,14 +221,18 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
         __syncthreads();   // the previous step's readers of the shared step data are done
         p = st.p0 + S % 4;
     } else {
-        key = wave_min_key(key);
-        if (lane == 0) sh.red_k[S & 1][wave] = key;
+        {
+            const unsigned ws = wave_umin(cs);
+            const unsigned wi = wave_umin(cs == ws ? ci : ~0u);
+            if (lane == 0) sh.red_k[S & 1][wave] = ((unsigned long long)ws << 32) | wi;
+        }
         OBC_TICK(1);   // selection + wave reduction
         __syncthreads();
         OBC_TICK(2);   // barrier 1
-        key = row16_min_key((lane & 15) < NW ? sh.red_k[S & 1][lane & 15] : ~0ull);
-        if (key == ~0ull) return 2;
-        p = (int)(unsigned)key;
+        const unsigned long long wk = (lane & 15) < NW ? sh.red_k[S & 1][lane & 15] : ~0ull;
+        const unsigned gs = row16_umin_all((unsigned)(wk >> 32));
+        if (gs == ~0u) return 2;
+        p = (int)row16_umin_all((unsigned)(wk >> 32) == gs ? (unsigned)wk : ~0u);
         if constexpr (MODE == MODE_BLOCK) st.p0 = p;
     }
 
@@ -247,7 +244,9 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
     for (int e = 0; e < EPT; ++e) {
         int j = tid + e * T;
         const int hi = (j <= p) ? p : j, lo = (j <= p) ? j : p;
-        size_t off = pr.swz ? quad_index(hi, lo, pr.ld) : (size_t)hi * pr.ld + lo;
+        // (a row's matrix has at most 4608^2 entries: 32-bit index arithmetic)
+        const unsigned off = pr.swz ? (((unsigned)(hi >> 2) * (unsigned)pr.ld + (unsigned)lo) << 2) + (unsigned)(hi & 3)
+                                    : (unsigned)hi * (unsigned)pr.ld + (unsigned)lo;
         col[e] = (j < pr.m) ? __builtin_nontemporal_load(&pr.Acur[off]) : 0.f;
     }
     // the owner of p publishes the pivot's data, the step's scalars and the coefficients
@@ -278,19 +277,29 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
         sh.bc_ok = ok ? 1 : 0;
         sh.pivs[S] = p;
         sh.invd_s[S] = (float)invapp;
+        // coefficients of the vectors kept in registers: only the owner has their entry p.  One
+        // branch per owned element, then four coefficients per LDS read / write.
+        constexpr int SREG = S < BR ? S : BR;
 #pragma unroll
-        for (int r = 0; r < S; ++r) {
-            float ur = 0.f;
-            if (r < BR) {
+        for (int e = 0; e < EPT; ++e) {
+            if (e != ep) continue;
 #pragma unroll
-                for (int e = 0; e < EPT; ++e)
-                    if (e == ep) ur = st.u[r < BR ? r : 0][e];
-            } else {
-                ur = ul[(r - BR) * CAP + p];
+            for (int r4 = 0; r4 < SREG; r4 += 4) {
+                const float4 iv = *reinterpret_cast<const float4 *>(&sh.invd_s[r4]);
+                float4 v;
+                v.x = __fmul_rn(st.u[r4][e], iv.x);
+                v.y = (r4 + 1 < SREG) ? __fmul_rn(st.u[r4 + 1 < BR ? r4 + 1 : 0][e], iv.y) : 0.f;
+                v.z = (r4 + 2 < SREG) ? __fmul_rn(st.u[r4 + 2 < BR ? r4 + 2 : 0][e], iv.z) : 0.f;
+                v.w = (r4 + 3 < SREG) ? __fmul_rn(st.u[r4 + 3 < BR ? r4 + 3 : 0][e], iv.w) : 0.f;
+                *reinterpret_cast<float4 *>(&sh.cvec[r4]) = v;
             }
-            sh.cvec[r] = __fmul_rn(ur, sh.invd_s[r]);
         }
         if (a.nm_m > 0 && op >= 0) blk[op / a.nm_m] += 1;
+    }
+    // coefficients of the vectors kept in LDS: one lane each
+    if constexpr (S > BR) {
+        const int r = BR + tid;
+        if (r < S) sh.cvec[r] = __fmul_rn(ul[(r - BR) * CAP + p], sh.invd_s[r]);
     }
     OBC_TICK(3);   // cross-wave reduction, load issue, owner's publication
     __syncthreads();
