@@ -78,6 +78,7 @@ struct PanelArgs {
 OBC_DECLARE_PANEL(256, 1, 64, 0);
 OBC_DECLARE_PANEL(256, 3, 32, 16);
 OBC_DECLARE_PANEL(1024, 1, 64, 0);
+OBC_DECLARE_PANEL(512, 3, 48, 16);
 OBC_DECLARE_PANEL(512, 4, 40, 16);
 OBC_DECLARE_PANEL(768, 3, 32, 16);
 OBC_DECLARE_PANEL(768, 4, 24, 12);

@@ -534,7 +534,7 @@ struct Variant {
       launch_panel_block_##T##_##EPT##_##BR##_##BL }
 
 const Variant kVariants[] = {
-    OBC_VARIANT(256, 1, 64, 0),   OBC_VARIANT(1024, 1, 64, 0), OBC_VARIANT(512, 4, 40, 16),
+    OBC_VARIANT(256, 1, 64, 0),   OBC_VARIANT(1024, 1, 64, 0), OBC_VARIANT(512, 3, 48, 16),  OBC_VARIANT(512, 4, 40, 16),
     OBC_VARIANT(768, 3, 32, 16),  OBC_VARIANT(768, 4, 24, 12), OBC_VARIANT(768, 6, 16, 8),
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
