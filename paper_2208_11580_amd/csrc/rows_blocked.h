@@ -81,7 +81,7 @@ OBC_DECLARE_PANEL(1024, 1, 64, 0);
 OBC_DECLARE_PANEL(512, 3, 48, 16);
 OBC_DECLARE_PANEL(512, 4, 40, 16);
 OBC_DECLARE_PANEL(768, 3, 32, 16);
-OBC_DECLARE_PANEL(768, 4, 24, 12);
+OBC_DECLARE_PANEL(512, 6, 28, 12);
 OBC_DECLARE_PANEL(768, 6, 16, 8);
 
 }  // namespace obc_blocked
