@@ -321,6 +321,14 @@ struct FlushArgs {
 typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 constexpr unsigned kBufWord3 = 0x00020000u;   // raw buffer, 32-bit data format
 constexpr int kFar = 0x40000000;              // byte offset beyond any matrix: "out of range"
+// Cache policy bits of the matrix accesses (gfx950 buffer instructions: 1 = sc0, 2 = nt, 16 = sc1).
+// The new matrix is written once and next read by another kernel: streaming stores keep it from
+// displacing the U tiles and the old matrix's lines in L2 (flush 19.9 -> 18.9 ms on the 256 x 2304
+// layer; nt, sc0+nt and sc1+nt within 1 % of each other, sc bits alone no change).  The loads stay
+// cached: a lane's four rows of a column share sectors over four consecutive loads, and streaming
+// loads made the kernel 25 % slower.
+constexpr int kMatLoadPolicy = 0;
+constexpr int kMatStorePolicy = 2 | 16;
 
 // K is the block size: every row that still has steps to do has exactly K deferred eliminations
 // (a row with fewer has finished and is skipped).  A strip is HALVES x 128 rows tall: the U tile
@@ -426,7 +434,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 int ro = rowoff_s[rb + wm * 64 + mt * 32 + 8 * (v >> 2) + lrow + (v & 3)];
-                c[mt][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rold, ro + joldB, 0, 0));
+                c[mt][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rold, ro + joldB, 0, kMatLoadPolicy));
             }
     };
     // the diagonal tile: only entries on or below the diagonal exist
@@ -438,7 +446,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                 int oi = rowold_s[rb + wm * 64 + mt * 32 + 8 * (v >> 2) + lrow + (v & 3)];
                 int off = (jold < 0 || jold > oi) ? kFar
                           : swz ? (((oi >> 2) * ldo + jold) * 4 + (oi & 3)) * 4 : (oi * ldo + jold) * 4;
-                c[mt][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rold, off, 0, 0));
+                c[mt][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rold, off, 0, kMatLoadPolicy));
             }
     };
     auto old_col = [&](int j) { return (j < mn) ? map[j] : -1; };
@@ -506,7 +514,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                 if (on_diag && jcol > qrow + 3) continue;                   // wholly above the diagonal
                 uintx4 v4 = {__float_as_uint(acc[mt][4 * q]), __float_as_uint(acc[mt][4 * q + 1]),
                              __float_as_uint(acc[mt][4 * q + 2]), __float_as_uint(acc[mt][4 * q + 3])};
-                __builtin_amdgcn_raw_buffer_store_b128(v4, rnew, quad * ldn * 16 + colB, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(v4, rnew, quad * ldn * 16 + colB, 0, kMatStorePolicy);
             }
         if (!more) break;
         if (new_col) {
