@@ -125,9 +125,22 @@ __global__ __launch_bounds__(256) void blocked_init_kernel(InitArgs a)
     }
 }
 
+// p[0 .. n) = v with 16-byte streaming stores; the floats before the first 16-byte boundary and
+// after the last one singly (p is 4-byte aligned)
 __global__ __launch_bounds__(256) void fill_f32_kernel(float *p, size_t n, float v)
 {
-    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n; e += (size_t)gridDim.x * 256) p[e] = v;
+    typedef float floatx4 __attribute__((ext_vector_type(4)));
+    size_t head = ((16 - ((uintptr_t)p & 15)) & 15) / 4;
+    if (head > n) head = n;
+    const floatx4 v4 = {v, v, v, v};
+    floatx4 *p4 = reinterpret_cast<floatx4 *>(p + head);
+    const size_t n4 = (n - head) / 4, tail = (n - head) % 4;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n4; e += (size_t)gridDim.x * 256)
+        __builtin_nontemporal_store(v4, p4 + e);
+    if (blockIdx.x == 0) {
+        if (threadIdx.x < head) p[threadIdx.x] = v;
+        if (threadIdx.x < tail) p[head + n4 * 4 + threadIdx.x] = v;
+    }
 }
 
 // ------------------------------------------------------------ bulk elimination of pruned indices
@@ -591,8 +604,9 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
     OBC_LAUNCH_CHECK(ctx, "blocked_init_kernel");
     if (trace && k_steps > 0) {
         size_t n = (size_t)R * out_ld * d;
-        unsigned blocks = (unsigned)((n + 256 * 16 - 1) / (256 * 16));
+        unsigned blocks = (unsigned)((n / 4 + 256 * 8 - 1) / (256 * 8));
         if (blocks > 65535) blocks = 65535;
+        if (blocks == 0) blocks = 1;
         fill_f32_kernel<<<blocks, 256, 0, st>>>(trace, n, 0.f);
         OBC_LAUNCH_CHECK(ctx, "fill_f32_kernel");
     }

@@ -558,6 +558,26 @@ def test_rows_that_do_no_step_keep_their_weights(obc, strategy):
     assert torch.equal(none["W"], W)
 
 
+def test_trace_of_an_odd_width_is_fully_written(obc, orc):
+    # the trace is cleared by a 16-byte-wide fill before the steps scatter into it: a size that is
+    # no multiple of four floats, over memory that held NaNs before
+    W, X = _layer("conv64x576", d_col=301, d_row=3, n_samples=1500)
+    Hinv = _hinv(obc, X)
+    poison = torch.full((3 * 301 * 301 + 64,), float("nan"), device="cuda")
+    del poison
+    res = obc.obc_prune_rows(W, Hinv, strategy=2, want_trace=True)
+    obc.obc_check()
+    tr = _np(res["trace"])
+    assert np.isfinite(tr).all()
+    order = _np(res["order"])
+    for i in range(3):
+        r = orc.prune_row(_np(Hinv).astype(np.float64), _np(W[i]).astype(np.float64), forced=order[i].astype(np.int32),
+                          want_trace=True)
+        for t in (0, 1, 150, 299, 300):
+            assert np.all(tr[i, t, order[i, :t + 1]] == 0.0)
+            assert np.linalg.norm(tr[i, t] - r.trace[t]) <= 1e-4 * np.linalg.norm(r.trace[t]) + 1e-30
+
+
 # ------------------------------------------------------------------------------ boundary errors
 def test_argument_errors(obc):
     import paper_2208_11580_amd as pkg
