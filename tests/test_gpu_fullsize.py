@@ -302,3 +302,18 @@ def test_width_4608_quantize_survivors(obc, orc):
     assert torch.all(q["W"][live == 0] == 0) and torch.all(q["codes"][live == 0] == -1)
     c = q["codes"]
     assert int(c[live != 0].min()) >= 0 and int(c[live != 0].max()) <= maxq
+
+
+def test_width_2400_block_pruning_first_blocks(obc, orc):
+    """Block pruning (blocks of 4) above 2304 columns runs on the panel variant with six owned indices
+    per thread and 40-step blocks; the oracle replays the first 30 block steps (three such blocks of
+    steps) of one row."""
+    W, X, _ = obc_inputs.make_layer("ffn768x3072", device="cuda", d_row=2, d_col=2400, n_samples=8000)
+    R, d = W.shape
+    assert d == 2400
+    Hinv = obc.obc_invert(obc.obc_hessian(X))
+    kb = 30
+    res = obc.obc_prune_blocks(W, Hinv, 4, k_blocks=kb)
+    obc.obc_check()
+    check_block_row(orc, _np(Hinv), _np(W[1]), 4, _np(res["order"][1]), _np(res["loss"][1]), _np(res["W"][1]), kb)
+    assert int((res["W"] == 0).sum()) == R * kb * 4
