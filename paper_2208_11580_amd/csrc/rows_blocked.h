@@ -82,6 +82,7 @@ OBC_DECLARE_PANEL(512, 3, 48, 16);
 OBC_DECLARE_PANEL(512, 4, 40, 16);
 OBC_DECLARE_PANEL(768, 3, 32, 16);
 OBC_DECLARE_PANEL(512, 6, 28, 12);
-OBC_DECLARE_PANEL(768, 6, 16, 8);
+OBC_DECLARE_PANEL(512, 8, 20, 8);
+OBC_DECLARE_PANEL(512, 9, 16, 8);
 
 }  // namespace obc_blocked

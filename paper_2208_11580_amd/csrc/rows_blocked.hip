@@ -556,7 +556,7 @@ struct Variant {
 
 const Variant kVariants[] = {
     OBC_VARIANT(256, 1, 64, 0),   OBC_VARIANT(1024, 1, 64, 0), OBC_VARIANT(512, 3, 48, 16),  OBC_VARIANT(512, 4, 40, 16),
-    OBC_VARIANT(768, 3, 32, 16),  OBC_VARIANT(512, 6, 28, 12), OBC_VARIANT(768, 6, 16, 8),
+    OBC_VARIANT(768, 3, 32, 16),  OBC_VARIANT(512, 6, 28, 12), OBC_VARIANT(512, 8, 20, 8),   OBC_VARIANT(512, 9, 16, 8),
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -654,6 +654,7 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
             const dim3 grid(fa.strips * rows8);
             switch (K) {
             case 24: flush_kernel<24, 2><<<grid, 512, 0, st>>>(fa); break;
+            case 28: flush_kernel<28, 2><<<grid, 512, 0, st>>>(fa); break;
             case 40: flush_kernel<40, 2><<<grid, 512, 0, st>>>(fa); break;
             case 48: flush_kernel<48, 2><<<grid, 512, 0, st>>>(fa); break;
             case 56: flush_kernel<56, 1><<<grid, 512, 0, st>>>(fa); break;

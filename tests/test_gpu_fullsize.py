@@ -251,7 +251,7 @@ def test_conv256x2304_sequential_obq_with_outlier_heuristic(obc, orc):
 
 
 def test_width_4608_first_blocks(obc, orc):
-    """The widest layer of the workloads (d_col = 4608) uses the panel variant with six owned
+    """The widest layer of the workloads (d_col = 4608) uses the panel variant with nine owned
     indices per thread and blocks of 24; the oracle replays the first 240 steps of one row."""
     W, X, _ = obc_inputs.make_layer("conv512x4608", device="cuda", d_row=3, n_samples=12000)
     R, d = W.shape
