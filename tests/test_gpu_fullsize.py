@@ -304,15 +304,15 @@ def test_width_4608_quantize_survivors(obc, orc):
     assert int(c[live != 0].min()) >= 0 and int(c[live != 0].max()) <= maxq
 
 
-def test_width_2400_block_pruning_first_blocks(obc, orc):
-    """Block pruning (blocks of 4) above 2304 columns runs on the panel variant with six owned indices
-    per thread and 40-step blocks; the oracle replays the first 30 block steps (three such blocks of
-    steps) of one row."""
-    W, X, _ = obc_inputs.make_layer("ffn768x3072", device="cuda", d_row=2, d_col=2400, n_samples=8000)
+@pytest.mark.parametrize("d_col,kb", [(2400, 30), (3200, 14), (4200, 12)])
+def test_wide_block_pruning_first_blocks(obc, orc, d_col, kb):
+    """Block pruning (blocks of 4) above 2304 columns runs on the panel variants with six, eight and
+    nine owned indices per thread (blocks of 40, 28 and 24 steps); the oracle replays the first
+    block steps (two to three such blocks of steps) of one row."""
+    W, X, _ = obc_inputs.make_layer("ffn768x3072", device="cuda", d_row=2, d_col=d_col, n_samples=8000)
     R, d = W.shape
-    assert d == 2400
+    assert d == d_col
     Hinv = obc.obc_invert(obc.obc_hessian(X))
-    kb = 30
     res = obc.obc_prune_blocks(W, Hinv, 4, k_blocks=kb)
     obc.obc_check()
     check_block_row(orc, _np(Hinv), _np(W[1]), 4, _np(res["order"][1]), _np(res["loss"][1]), _np(res["W"][1]), kb)
