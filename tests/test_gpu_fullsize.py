@@ -317,3 +317,19 @@ def test_wide_block_pruning_first_blocks(obc, orc, d_col, kb):
     obc.obc_check()
     check_block_row(orc, _np(Hinv), _np(W[1]), 4, _np(res["order"][1]), _np(res["loss"][1]), _np(res["W"][1]), kb)
     assert int((res["W"] == 0).sum()) == R * kb * 4
+
+
+def test_width_3200_first_steps(obc, orc):
+    """Live sizes 3073..4096 run on the panel variant with eight owned indices per thread and blocks of
+    28 steps; the oracle replays the first 60 steps (two blocks and a flush each, then a part) of one
+    row."""
+    W, X, _ = obc_inputs.make_layer("ffn768x3072", device="cuda", d_row=2, d_col=3200, n_samples=8000)
+    Hinv = obc.obc_invert(obc.obc_hessian(X))
+    k = 60
+    res = obc.obc_prune_rows(W, Hinv, k_steps=k)
+    obc.obc_check()
+    st = RowParity()
+    check_row(orc, st, "prune", _np(Hinv), _np(W[0]), _np(res["order"][0]), _np(res["loss"][0]),
+              _np(res["W"][0]), k)
+    print(st)
+    assert int((res["W"] == 0).sum()) == 2 * k
