@@ -717,3 +717,40 @@ def test_block_rows_driver_and_argument_checks(orc):
         orc.block_prune_row(A, W[0], 5)          # d not a multiple of c
     with pytest.raises(Exception):
         orc.block_prune_row(A, W[0], 4, k_blocks=4)
+
+
+# ----------------------------------------------------------------------------- layer objective
+def test_layer_error_is_the_sum_of_squared_output_differences(orc):
+    """Sec. 3 eq. (2): ||W X - W^ X||^2, spelled out per output row and per sample."""
+    rng = np.random.default_rng(70)
+    R, d, n = 3, 5, 7
+    W = rng.standard_normal((R, d))
+    Wh = W + 0.3 * rng.standard_normal((R, d))
+    X = rng.standard_normal((d, n))
+    total = 0.0
+    for i in range(R):
+        for s in range(n):
+            y = sum(W[i, j] * X[j, s] for j in range(d))
+            yh = sum(Wh[i, j] * X[j, s] for j in range(d))
+            total += (y - yh) ** 2
+    assert np.isclose(orc.layer_error(W, Wh, X), total, rtol=1e-12)
+    # hand value: W - W^ = [[1, -2]], X = [[1, 2], [3, 4]]: outputs differ by (-5, -6): 25 + 36
+    assert orc.layer_error(np.array([[2.0, 0.0]]), np.array([[1.0, 2.0]]), np.array([[1.0, 2.0], [3.0, 4.0]])) == 61.0
+    # one row's share and the whole layer's are not the same thing (sum over rows), nor is it a norm
+    # without the square
+    assert orc.layer_error(W, Wh, X) > orc.layer_error(W[:1], Wh[:1], X)
+    assert np.isclose(orc.layer_error(W, W + 2.0 * (Wh - W), X), 4.0 * total, rtol=1e-12)
+    assert orc.layer_error(W, W, X) == 0.0
+
+
+def test_layer_error_equals_accumulated_loss_changes_without_dampening(orc):
+    """With lambda = 0 the recorded loss changes w_p^2 / (2 [H^-1]_pp) of Sec. 4 add up, over all
+    steps of all rows, to the layer objective of eq. (2) evaluated from X."""
+    W, X = _problem(71, 12, n=60, R=4)
+    H = orc.hessian(X, damp_rel=-1)
+    A = orc.invert(H)
+    res = orc.prune_rows(A, W, k_steps=7)
+    assert np.isclose(orc.layer_error(W, res["W"], X), res["loss"].sum(), rtol=1e-8)
+    grids = [orc.minmax_grid(W[i], 3) for i in range(W.shape[0])]
+    q = orc.quant_rows(A, W, [g[0] for g in grids], [g[1] for g in grids], grids[0][2])
+    assert np.isclose(orc.layer_error(W, q["W"], X), q["loss"].sum(), rtol=1e-8)
