@@ -4,10 +4,12 @@
 One "step" is one pass of the whole path over one synthetic layer that is already resident in
 HBM: obc_hessian -> obc_invert -> (grid) -> per-row greedy solver -> (global step + gather for
 unstructured pruning).  Prints ONE JSON line: whole-path row-steps/s, the roofline of the
-dominant kernel measured with events on the library's stream, and the CPU oracle timed on a
-bounded sample of the same workload.
+dominant kernel measured with events on the library's stream, the same figures for the second
+layer the performance target names (768 x 3072), and the CPU oracle timed on a bounded sample of
+the headline workload.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--strategy auto|rank1|blocked]
+    python bench.py --membench        # the plain read / write / copy kernels' GB/s instead
 """
 import argparse
 import json
@@ -40,43 +42,28 @@ WORKLOADS = {
     "conv256x2304-seqobq4": ("conv256x2304", "seqobq4"),
 }
 DEFAULT_WORKLOAD = "conv256x2304-obq4"
+SECOND_WORKLOAD = "ffn768x3072-prune50"     # the other layer the target quotes its roofline figure on
 HBM_PEAK_GBS = 8000.0
 MFMA_F32_PEAK_TFLOPS = 157.3
+# fp32 vector peak of the code as it is compiled here: 256 compute units x 4 SIMDs x 16 lanes x 2 flop
+# (one FMA) x 2.4 GHz = 78.6 TFLOP/s.  The published 157.3 TFLOP/s counts two FMAs per lane and clock,
+# which only the packed fp32 instructions reach; the library is built with them switched off.
+VALU_F32_PEAK_TFLOPS = 256 * 4 * 16 * 2 * 2.4e9 / 1e12
+BC = 4                                      # block size of the block-pruning workloads
+NAMES = {"flush": "flush_kernel", "panel": "panel_kernel", "rank1": "rows_rank1_kernel"}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(WORKLOADS))
-    ap.add_argument("--strategy", default="auto", choices=["auto", "rank1", "blocked"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=0, help="rows in the oracle sample (0 = one per host thread)")
-    ap.add_argument("--calib-copy", action="store_true",
-                    help="after the timed region run one plain 1 GiB device copy (calibrates rocprofv3's "
-                         "FETCH_SIZE / WRITE_SIZE counters against a kernel of known traffic)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU (the row solver shards trivially over rows, "
-                 "but no multi-GPU path exists here); run with --gpus 1")
-
+def run_workload(ctx, pkg, workload, steps, warmup, strategy):
+    """Time `steps` passes of the whole path on one layer; returns the figures and what the oracle leg needs."""
     import numpy as np
     import torch
 
     import obc_inputs
-    import paper_2208_11580_amd as pkg
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    layer, task = WORKLOADS[args.workload]
-    strategy = {"auto": pkg.STRATEGY_AUTO, "rank1": pkg.STRATEGY_RANK1, "blocked": pkg.STRATEGY_BLOCKED}[args.strategy]
+    layer, task = WORKLOADS[workload]
     W, X, spec = obc_inputs.make_layer(layer, device="cuda:0")
     R, d = W.shape
     N = X.shape[1]
-    ctx = pkg.Context()
-
-    BC = 4
     if task.startswith("block"):
         sparsity = int(task[-2:]) / 100.0
         k_steps, nm = d // BC, (0, 0)      # block steps per row
@@ -98,6 +85,7 @@ def main():
                W=torch.empty(R, d, device="cuda"))
     if task.endswith("obq4"):
         out["codes"] = torch.empty(R, d, dtype=torch.int32, device="cuda")
+    Wfit = None
     if task == "seqobq4":
         # stand-in for the inputs of the already compressed model: the dense inputs, perturbed;
         # Y = the dense layer's outputs on the dense inputs
@@ -120,6 +108,7 @@ def main():
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
     stage_ms = {"hessian": [], "invert": [], "rows": [], "global": []}
+    grid = {}
 
     def one_step(record):
         e = [ev() for _ in range(5)]
@@ -134,11 +123,13 @@ def main():
         e[2].record()
         if task == "seqobq4":
             delta, offset, maxq = ctx.obc_minmax_grid(Wfit, 4)
+            grid.update(delta=delta, offset=offset, maxq=maxq)
             res = ctx.obc_quant_rows(Wfit, H, delta, offset, maxq, strategy=strategy, out=out)
         elif task.startswith("block"):
             res = ctx.obc_prune_blocks(W, H, BC, want_trace=want_trace, strategy=strategy)
         elif task.startswith("obq"):
             delta, offset, maxq = ctx.obc_minmax_grid(W, 4)
+            grid.update(delta=delta, offset=offset, maxq=maxq)
             res = ctx.obc_quant_rows(W, H, delta, offset, maxq, strategy=strategy, out=out)
         else:
             res = ctx.obc_prune_rows(W, H, k_steps=k_steps, nm=nm, want_trace=want_trace,
@@ -150,6 +141,7 @@ def main():
             counts, mask = ctx.obc_global_select(res["loss"], res["order"], k)
             result = ctx.obc_gather_trace(W, res["trace"], counts)
             out["order"] = res["order"]
+            out["loss"] = res["loss"]
         elif task.startswith("prune") or task.startswith("compound"):
             k = obc_inputs.target_count(sparsity, R, d)
             counts, mask = ctx.obc_global_select(res["loss"], res["order"], k)
@@ -168,26 +160,18 @@ def main():
                 stage_ms[name].append(e[a].elapsed_time(e[b]))
         return result
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         one_step(False)
     ctx.obc_check()
     torch.cuda.synchronize()
     ctx.obc_profile_begin()       # events around every row-solver launch, on the library's stream
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        result = one_step(True)
+    for _ in range(steps):
+        one_step(True)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     kstats = ctx.obc_profile_end()
     ctx.obc_check()
-    ms_per_step = 1e3 * wall / args.steps
-    value = row_steps / (wall / args.steps)
-    if args.calib_copy:
-        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB read, 1 GiB written
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
 
     # ---- roofline of the dominant kernel of the row solver, from the events the library recorded
     # around each of its launches during the timed steps.  Algorithmic bytes / flops per launch are
@@ -196,76 +180,193 @@ def main():
     kern = {k: v for k, v in kstats.items() if v["launches"] > 0}
     dom = max(kern, key=lambda k: kern[k]["ms"])
     ds = kern[dom]
-    per_launch_ms = ds["ms"] / ds["launches"]
     gbs = ds["bytes"] / (1e-3 * ds["ms"]) / 1e9 if ds["ms"] > 0 else 0.0
     tfs = ds["flops"] / (1e-3 * ds["ms"]) / 1e12 if ds["ms"] > 0 else 0.0
-    names = {"flush": "flush_kernel", "panel": "panel_kernel", "rank1": "rows_rank1_kernel"}
     if dom == "rank1" and ds["bytes"] == 0:      # LDS-resident: bounded by the fp32 vector units
-        roofline = {"bound": "alu", "kernel": names[dom], "achieved": tfs, "peak": 78.6, "unit": "TFLOP/s",
-                    "frac": tfs / 78.6, "traffic": None}
+        roofline = {"bound": "alu", "kernel": NAMES[dom], "achieved": tfs, "peak": VALU_F32_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": tfs / VALU_F32_PEAK_TFLOPS, "traffic": None}
     else:
-        roofline = {"bound": "hbm", "kernel": names[dom], "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        roofline = {"bound": "hbm", "kernel": NAMES[dom], "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": gbs / HBM_PEAK_GBS, "traffic": None}
     # measured HBM bytes per launch of the dominant kernel, from the stored rocprofv3 counter runs of
     # this same command (profiles/hbm_traffic_<workload>.txt), when such a summary exists
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % args.workload.replace("-", "_"))
-    if os.path.exists(tpath) and args.strategy == "auto":
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload.replace("-", "_"))
+    if os.path.exists(tpath) and strategy == pkg.STRATEGY_AUTO:
         for ln in open(tpath):
-            if ln.startswith("family %s " % names[dom]):
+            if ln.startswith("family %s " % NAMES[dom]):
                 roofline["traffic"] = float(ln.split("traffic_bytes_per_launch=")[1].split()[0])
+    # the row solver as a whole: the algorithmic bytes of all its launches (panels and flushes, the
+    # schedule they implement) over the time of the whole rows call; and, for context, the bytes the
+    # literal Algorithm 1 would move (read + write the whole d x d matrix every step: 8 d^2 per
+    # row-step) over the same time -- an equivalent rate, far above the peak because the blocked,
+    # symmetric, shrinking schedule moves that many fewer bytes
+    solver_bytes = sum(v["bytes"] for v in kern.values()) / steps
+    literal_bytes = 8.0 * d * d * float(row_steps)
     roofline.update({
-        "launches_per_step": ds["launches"] / args.steps, "avg_launch_ms": per_launch_ms,
+        "launches_per_step": ds["launches"] / steps, "avg_launch_ms": ds["ms"] / ds["launches"],
         "alg_bytes_per_launch": ds["bytes"] / ds["launches"], "mfma_tflops": tfs,
         "mfma_frac": tfs / MFMA_F32_PEAK_TFLOPS,
-        "share_of_rows_time": ds["ms"] / args.steps / (1e3 * rows_s),
+        "share_of_rows_time": ds["ms"] / steps / (1e3 * rows_s),
         "row_steps_per_s_rows_call": row_steps / rows_s,
-        "kernels": {names[k]: {"launches_per_step": v["launches"] / args.steps, "ms_per_step": v["ms"] / args.steps,
+        "solver": {"alg_bytes_per_step": solver_bytes, "rows_call_ms": 1e3 * rows_s,
+                   "GB/s": solver_bytes / rows_s / 1e9, "frac": solver_bytes / rows_s / 1e9 / HBM_PEAK_GBS},
+        "literal_S": {"bytes_per_step": literal_bytes, "equiv_GB/s": literal_bytes / rows_s / 1e9,
+                      "equiv_frac": literal_bytes / rows_s / 1e9 / HBM_PEAK_GBS},
+        "kernels": {NAMES[k]: {"launches_per_step": v["launches"] / steps, "ms_per_step": v["ms"] / steps,
                                "GB/s": v["bytes"] / (1e-3 * v["ms"]) / 1e9, "TFLOP/s": v["flops"] / (1e-3 * v["ms"]) / 1e12}
                     for k, v in kern.items()},
     })
+    hess_tf = float(d) * d * N / (1e-3 * float(np.mean(stage_ms["hessian"]))) / 1e12   # useful flops: one triangle
+    return dict(workload=workload, task=task, R=R, d=d, N=N, k_steps=k_steps, nm=nm, row_steps=row_steps,
+                ms_per_step=1e3 * wall / steps, value=row_steps / (wall / steps),
+                stages_ms={k: float(np.mean(v)) for k, v in stage_ms.items() if v}, roofline=roofline,
+                hessian_mfma_frac=hess_tf / MFMA_F32_PEAK_TFLOPS,
+                W=(Wfit if task == "seqobq4" else W), Hinv=H, out=out, grid=grid)
+
+
+def oracle_leg(r, cpu_rows):
+    """The oracle on the host cores over a bounded sample of rows, fed what the GPU solver was fed
+    (its fp32 inverse Hessian, weights and grid), and the agreement of the two on those rows."""
+    import numpy as np
+
+    from oracle import oracle as orc
+
+    task, R, d, k_steps, nm = r["task"], r["R"], r["d"], r["k_steps"], r["nm"]
+    block = task.startswith("block")
+    threads = min(os.cpu_count() or 1, 16)
+    # keep the sample to roughly 10-30 s: the oracle costs ~ k d^2 / 3 inner iterations per row
+    per_row_s = (k_steps * (BC if block else 1) * d * d / 3.0) / 0.7e9
+    n_rows = cpu_rows or threads * max(1, int(round(15.0 / max(per_row_s, 1e-9))))
+    n_rows = min(n_rows, R)
+    while n_rows > threads and per_row_s * n_rows / threads > 30:
+        n_rows //= 2
+    A64 = r["Hinv"].cpu().numpy().astype(np.float64)
+    Wn = r["W"][:n_rows].cpu().numpy().astype(np.float64)
+    quant = task.endswith("obq4")
+    if quant:
+        dl = r["grid"]["delta"][:n_rows].cpu().numpy().astype(np.float64)
+        of = r["grid"]["offset"][:n_rows].cpu().numpy().astype(np.float64)
+        maxq = r["grid"]["maxq"]
+    t1 = time.perf_counter()
+    if block:
+        ro = orc.block_prune_rows(A64, Wn, BC, n_threads=threads)
+    elif quant:
+        ro = orc.quant_rows(A64, Wn, dl, of, maxq, n_threads=threads)
+    else:
+        ro = orc.prune_rows(A64, Wn, k_steps=k_steps, nm=nm, n_threads=threads)
+    cpu_s = time.perf_counter() - t1
+    base = {
+        "value": n_rows * k_steps * (BC if block else 1) / cpu_s, "unit": "row-steps/s", "cores": int(ro["threads"]),
+        "kind": "oracle", "sample": "%d of %d rows of %s, all %d steps each, %.1f s" % (
+            n_rows, R, r["workload"], k_steps, cpu_s),
+    }
+    # Agreement of the timed GPU result with the oracle on the sampled rows (outside the timed
+    # part).  Orders are compared entry by entry; a row whose order differs is replayed by the
+    # oracle along the GPU's order, and every GPU pick must then score within 1e-6 relative of the
+    # oracle's minimum at that step (two near-tied picks taken in the other order give the same
+    # state two steps later).
+    g_order = r["out"]["order"][:n_rows].cpu().numpy()
+    same = g_order == ro["order"]
+    agree = {"order_entries_equal": float(np.mean(same)), "rows_with_swaps": 0, "near_ties": 0, "beyond_gap": 0}
+    bad_rows = [i for i in range(n_rows) if not same[i].all()]
+    agree["rows_with_swaps"] = len(bad_rows)
+    for i in bad_rows[:8]:                       # bounded: each replay is one more oracle row
+        f = g_order[i].astype(np.int32)
+        if block:
+            rr = orc.block_prune_row(A64, Wn[i], BC, forced=f)
+        elif quant:
+            rr = orc.quant_row(A64, Wn[i], (float(dl[i]), float(of[i]), maxq), forced=f)
+        else:
+            rr = orc.prune_row(A64, Wn[i], k_steps=k_steps, nm=nm, forced=f)
+        gap = rr.pick_score - rr.min_score
+        tol = 1e-6 * rr.min_score + 1e-12 * float(np.max(rr.min_score))
+        agree["near_ties"] += int(np.count_nonzero((gap > 0) & (gap <= tol)))
+        agree["beyond_gap"] += int(np.count_nonzero(gap > tol))
+    agree["rows_replayed"] = min(len(bad_rows), 8)
+    base["agreement"] = agree
+    return base
+
+
+def membench(ctx):
+    """GB/s of the library's plain read / write / copy kernels over 4 GiB buffers."""
+    import torch
+
+    nbytes = 4 << 30
+    src = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    res = {"bytes_per_buffer": nbytes}
+    for name, kind, streaming, moved in (("read", 0, False, nbytes), ("write", 1, False, nbytes),
+                                         ("write_streaming", 1, True, nbytes), ("copy", 2, False, 2 * nbytes),
+                                         ("copy_streaming", 2, True, 2 * nbytes)):
+        ms = ctx.obc_membench(kind, src, dst, nbytes, reps=5, streaming=streaming)
+        res[name] = {"ms": ms, "GB/s": moved / (1e-3 * ms) / 1e9, "frac_of_peak": moved / (1e-3 * ms) / 1e9 / HBM_PEAK_GBS}
+    print(json.dumps({"membench": res, "peak_GB/s": HBM_PEAK_GBS}))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(WORKLOADS))
+    ap.add_argument("--strategy", default="auto", choices=["auto", "rank1", "blocked"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-second-layer", action="store_true",
+                    help="skip the 768 x 3072 layer that the default run times after the headline workload")
+    ap.add_argument("--cpu-rows", type=int, default=0, help="rows in the oracle sample (0 = one per host thread)")
+    ap.add_argument("--membench", action="store_true", help="time the plain read / write / copy kernels and exit")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="after the timed region run one plain 1 GiB device copy (calibrates rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters against a kernel of known traffic)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (the row solver shards trivially over rows, "
+                 "but no multi-GPU path exists here); run with --gpus 1")
+
+    import torch
+
+    import paper_2208_11580_amd as pkg
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    ctx = pkg.Context()
+    if args.membench:
+        membench(ctx)
+        return
+    strategy = {"auto": pkg.STRATEGY_AUTO, "rank1": pkg.STRATEGY_RANK1, "blocked": pkg.STRATEGY_BLOCKED}[args.strategy]
+    r = run_workload(ctx, pkg, args.workload, args.steps, args.warmup, strategy)
+    if args.calib_copy:
+        nb = 1 << 30                                   # 1 GiB read, 1 GiB written
+        src = torch.zeros(nb, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        ctx.obc_membench(2, src, dst, nb, reps=1)      # (one warm-up + one timed launch of the copy kernel)
+        del src, dst
 
     line = {
         "metric": "ExactOBS row-steps/sec per layer + % fp32 VALU/HBM roofline, 1 MI355X",
-        "value": value, "unit": "row-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": r["value"], "unit": "row-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "d_row": R, "d_col": d, "n_samples": N, "task": task,
-                   "strategy": args.strategy, "row_steps": row_steps},
-        "stages_ms": {k: float(np.mean(v)) for k, v in stage_ms.items() if v},
-        "roofline": roofline,
+        "config": {"workload": args.workload, "d_row": r["R"], "d_col": r["d"], "n_samples": r["N"], "task": r["task"],
+                   "strategy": args.strategy, "row_steps": r["row_steps"]},
+        "stages_ms": r["stages_ms"],
+        "hessian_mfma_frac": r["hessian_mfma_frac"],
+        "roofline": r["roofline"],
     }
-
     # ---- the oracle on the host cores, on a bounded sample of rows of the same layer
     if not args.no_cpu_baseline:
-        from oracle import oracle as orc
-
-        threads = min(os.cpu_count() or 1, 16)
-        # keep the sample to roughly 10-30 s: the oracle costs ~ k d^2 / 3 inner iterations per row
-        per_row_s = (k_steps * (BC if task.startswith("block") else 1) * d * d / 3.0) / 0.7e9
-        n_rows = args.cpu_rows or threads * max(1, int(round(15.0 / max(per_row_s, 1e-9))))
-        n_rows = min(n_rows, R)
-        while n_rows > threads and per_row_s * n_rows / threads > 30:
-            n_rows //= 2
-        A64 = H.cpu().numpy().astype(np.float64)
-        Wn = (Wfit if task == "seqobq4" else W)[:n_rows].cpu().numpy().astype(np.float64)
-        t1 = time.perf_counter()
-        if task.startswith("block"):
-            ro = orc.block_prune_rows(A64, Wn, BC, n_threads=threads)
-        elif task.endswith("obq4"):
-            grids = [orc.minmax_grid(Wn[i], 4) for i in range(n_rows)]
-            ro = orc.quant_rows(A64, Wn, [g[0] for g in grids], [g[1] for g in grids], 15, n_threads=threads)
-        else:
-            ro = orc.prune_rows(A64, Wn, k_steps=k_steps, nm=nm, n_threads=threads)
-        cpu_s = time.perf_counter() - t1
-        line["cpu_baseline"] = {
-            "value": n_rows * k_steps * (BC if task.startswith("block") else 1) / cpu_s, "unit": "row-steps/s",
-            "cores": int(ro["threads"]),
-            "kind": "oracle", "sample": "%d of %d rows of %s, all %d steps each, %.1f s" % (
-                n_rows, R, args.workload, k_steps, cpu_s),
+        line["cpu_baseline"] = oracle_leg(r, args.cpu_rows)
+    # ---- the second layer of the target, same path, after the headline workload's buffers are gone
+    if args.workload == DEFAULT_WORKLOAD and args.strategy == "auto" and not args.no_second_layer:
+        del r
+        ctx.release_workspace()
+        torch.cuda.empty_cache()
+        s = run_workload(ctx, pkg, SECOND_WORKLOAD, min(args.steps, 3), min(args.warmup, 1), strategy)
+        line["second_layer"] = {
+            "workload": SECOND_WORKLOAD, "d_row": s["R"], "d_col": s["d"], "n_samples": s["N"],
+            "value": s["value"], "unit": "row-steps/s", "ms_per_step": s["ms_per_step"], "steps": min(args.steps, 3),
+            "stages_ms": s["stages_ms"], "hessian_mfma_frac": s["hessian_mfma_frac"], "roofline": s["roofline"],
         }
-        # sanity: the timed GPU result agrees with the oracle on the sampled rows
-        g_order = out["order"][:n_rows].cpu().numpy()
-        line["cpu_baseline"]["order_agreement"] = float(np.mean(g_order == ro["order"]))
     print(json.dumps(line))
 
 

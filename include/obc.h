@@ -86,6 +86,16 @@ typedef struct obc_kernel_stat {
 int obc_profile_begin(obc_ctx *ctx);
 int obc_profile_end(obc_ctx *ctx, obc_kernel_stat stats[OBC_KERNEL_CLASSES]);
 
+/* What this GPU's memory system gives the plainest kernels (16-byte accesses, every compute unit
+ * busy): kind 0 reads `bytes` from src, 1 writes `bytes` to dst, 2 copies src to dst; streaming != 0
+ * makes the stores non-temporal (as the row solver's matrix stores are).  Runs one warm-up pass and
+ * `reps` timed passes on the context's stream, waits, and returns the mean milliseconds per pass:
+ * the measured ceiling that HBM-bound kernels are compared with.  bytes must be a multiple of 16,
+ * the buffers 16-byte aligned; for kind 0 the buffer must hold words whose lowest bit is clear
+ * (e.g. all zero).  Synchronous. */
+int obc_membench(obc_ctx *ctx, int kind, int streaming, const void *src, void *dst, size_t bytes,
+                 int reps, double *ms_per_pass);
+
 /* ---- Sec. 4: H = 2 X X^T, "Implementation Details": dampening -------------------------
  * X: d x N fp32 with leading dimension ldx >= N (element (j, n) at X[j*ldx + n]).
  * H: d x d fp32.  accumulate == 0: H = 2 X X^T;  accumulate != 0: H += 2 X X^T (calibration
@@ -125,7 +135,8 @@ int obc_rows_workspace_bytes(int R, int d, int strategy, size_t *bytes);
  *   loss     R x k_steps fp32 out: loss change w_p^2 / (2 [H^-1]_pp) of each step
  *   W_out    R x d out: the row after its last step (pruned weights exactly 0)
  *   trace    nullable, R x k_steps x d out: the row after every step (the "pruning trace" of
- *            Sec. 4 Step 2, kept in HBM here)
+ *            Sec. 4 Step 2, kept in HBM here); entries of steps a row does not take (stop_counts,
+ *            fewer survivors than k_steps) are zero
  * Ties in the argmin go to the lowest index. */
 int obc_prune_rows(obc_ctx *ctx, const float *W, const float *Hinv, int R, int d, int k_steps,
                    int nm_n, int nm_m, const int32_t *stop_counts, const uint8_t *live, int32_t *order,
@@ -155,7 +166,9 @@ int obc_prune_blocks(obc_ctx *ctx, const float *W, const float *Hinv, int R, int
                                   over those weights only (same score, same tie rule) */
 
 /* Quantize every row with Algorithm 3 on the caller's per-row uniform grid
- *   q(w) = offset[i] + delta[i] * clamp(rne((w - offset[i]) / delta[i]), 0, maxq).
+ *   q(w) = offset[i] + delta[i] * clamp(rne((w - offset[i]) / delta[i]), 0, maxq)
+ * (rne = round half to even; the kernels evaluate the quotient in fp64 as a product with the fp64
+ * reciprocal of delta[i], in the candidate scores and when the chosen weight is written alike).
  *   flags    0 or OBC_QUANT_OUTLIERS
  *   live     nullable, R x d: 0 marks an already pruned weight; those are first removed from the
  *            row's inverse (Lemma 1, no weight change) so that OBQ runs on the dense sub-problem

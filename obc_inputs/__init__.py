@@ -17,6 +17,7 @@ pair always yields the same values.
 """
 from __future__ import annotations
 
+import functools
 import math
 from dataclasses import dataclass
 
@@ -58,11 +59,12 @@ def _gen(device, seed):
     return g
 
 
+@functools.lru_cache(maxsize=4)
 def mixing_matrix(d: int, seed: int, cond: float = 1e3) -> torch.Tensor:
     """A = U diag(s) V^T with orthogonal U, V (QR of Gaussians) and s log-spaced 1 .. 1/cond.
 
     Built on the CPU in fp64 so that the same matrix is used whatever device the rest of the
-    layer is generated on; returned as fp32.
+    layer is generated on; returned as fp32 (cached: callers must not modify it).
     """
     g = _gen("cpu", seed)
     G1 = torch.randn(d, d, generator=g, dtype=torch.float64)

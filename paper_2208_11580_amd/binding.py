@@ -24,7 +24,7 @@ QUANT_OUTLIERS = 1
 
 EXPORTS = [
     "obc_create", "obc_destroy", "obc_last_error", "obc_version", "obc_check",
-    "obc_profile_begin", "obc_profile_end",
+    "obc_profile_begin", "obc_profile_end", "obc_membench",
     "obc_hessian_workspace_bytes", "obc_hessian",
     "obc_invert_workspace_bytes", "obc_invert",
     "obc_cross_workspace_bytes", "obc_cross", "obc_refit_workspace_bytes", "obc_refit",
@@ -70,6 +70,7 @@ def load_library():
     lib.obc_check.argtypes = [vp]
     lib.obc_profile_begin.argtypes = [vp]
     lib.obc_profile_end.argtypes = [vp, POINTER(KernelStat)]
+    lib.obc_membench.argtypes = [vp, c_int, c_int, vp, vp, c_size_t, c_int, POINTER(ctypes.c_double)]
     lib.obc_hessian_workspace_bytes.argtypes = [c_int, c_int64, sp]
     lib.obc_hessian.argtypes = [vp, vp, c_int, c_int64, c_int64, c_float, c_int, vp, vp, c_size_t]
     lib.obc_invert_workspace_bytes.argtypes = [c_int, sp]
@@ -141,11 +142,17 @@ class Context:
         """A cached device byte buffer of at least nbytes (device memory is torch's job)."""
         nbytes = max(int(nbytes), 256)
         if self._ws is None or self._ws.numel() < nbytes:
+            if self._ws is not None:
+                # earlier calls queued on the context's stream may still use the old buffer: the
+                # allocator must not hand it out again before that stream has passed this point
+                self._ws.record_stream(self.stream)
             self._ws = None
             self._ws = torch.empty(nbytes, dtype=torch.uint8, device=torch.device("cuda", torch.cuda.current_device()))
         return self._ws
 
     def release_workspace(self):
+        if self._ws is not None:
+            self._ws.record_stream(self.stream)
         self._ws = None
 
     # ------------------------------------------------------------------ entry points
@@ -160,6 +167,13 @@ class Context:
         self._ck(self.lib.obc_profile_end(self.h, arr))
         return {name: dict(launches=arr[i].launches, ms=arr[i].ms, bytes=arr[i].bytes, flops=arr[i].flops)
                 for i, name in enumerate(KERNEL_CLASSES)}
+
+    def obc_membench(self, kind, src, dst, nbytes, reps=5, streaming=False):
+        """Mean milliseconds per pass of the plain read (0) / write (1) / copy (2) kernel."""
+        ms = ctypes.c_double()
+        self._ck(self.lib.obc_membench(self.h, int(kind), int(bool(streaming)), _ptr(src), _ptr(dst), int(nbytes),
+                                       int(reps), byref(ms)))
+        return ms.value
 
     def obc_hessian(self, X, damp_rel=0.01, H=None, accumulate=False):
         d, N = X.shape

@@ -2,31 +2,11 @@
 // one small translation unit per (threads, elements per thread, block size) variant.
 #pragma once
 
+#include <atomic>
+
 #include "rows_blocked.h"
 
 namespace obc_blocked {
-
-// Phase timing of the panel kernel for kernel development: compiled in only with
-// -DOBC_PANEL_TIMING; thread 0 of workgroup 0 accumulates shader-clock deltas per phase.
-#ifdef OBC_PANEL_TIMING
-#ifndef OBC_TICK_MIN_M
-#define OBC_TICK_MIN_M 0       // only launches with a live size above this are timed
-#endif
-#ifndef OBC_TICK_MAX_M
-#define OBC_TICK_MAX_M 0x7fffffff
-#endif
-extern __device__ unsigned long long obc_panel_timing[8];
-#define OBC_TICK(slot)                                                        \
-    do {                                                                      \
-        if (blockIdx.x == 0 && threadIdx.x == 0 && pr.m > OBC_TICK_MIN_M && pr.m <= OBC_TICK_MAX_M) { \
-            unsigned long long now__ = __builtin_readcyclecounter();          \
-            atomicAdd(&obc_panel_timing[slot], now__ - pr.tick);              \
-            const_cast<PanelRow &>(pr).tick = now__;                          \
-        }                                                                     \
-    } while (0)
-#else
-#define OBC_TICK(slot) do { } while (0)
-#endif
 
 // Per-thread state of the panel: everything indexed by the owned element e (compact index
 // tid + e*T) or by the step r inside the block.  All indices are compile-time constants once the
@@ -154,7 +134,6 @@ struct PanelRow {
     float *gU;
     int ld, swz, d, m, done, total, ndead, row;
     double qd, qo, qmax, iqd;
-    unsigned long long tick;
 };
 
 // One greedy step, S-th of the block.  Returns 0 to continue, 1 when the row has no step left,
@@ -168,7 +147,6 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
     constexpr int NW = T / 64;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (pr.done + S >= pr.total) return 1;
-    OBC_TICK(0);   // since the end of the previous step
 
     // ---- (1) selection.  The error (target - w) is formed in fp64 (for OBQ it is a difference of
     // nearby numbers); the score itself, error^2 / a_jj, is only compared, so it is taken in fp32
@@ -226,9 +204,7 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
             const unsigned wi = wave_umin(cs == ws ? ci : ~0u);
             if (lane == 0) sh.red_k[S & 1][wave] = ((unsigned long long)ws << 32) | wi;
         }
-        OBC_TICK(1);   // selection + wave reduction
         __syncthreads();
-        OBC_TICK(2);   // barrier 1
         const unsigned long long wk = (lane & 15) < NW ? sh.red_k[S & 1][lane & 15] : ~0ull;
         const unsigned gs = row16_umin_all((unsigned)(wk >> 32));
         if (gs == ~0u) return 2;
@@ -301,9 +277,7 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
         const int r = BR + tid;
         if (r < S) sh.cvec[r] = __fmul_rn(ul[(r - BR) * CAP + p], sh.invd_s[r]);
     }
-    OBC_TICK(3);   // cross-wave reduction, load issue, owner's publication
     __syncthreads();
-    OBC_TICK(4);   // barrier 2
     if (!sh.bc_ok) return 2;
     // the step's records are written here, while everybody waits for the fetched row anyway
     if (owner) {
@@ -372,7 +346,6 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
             }
         }
     }
-    OBC_TICK(5);   // wait for the row, correction, w / diag update
     if (MODE == MODE_BLOCK && a.trace && S % 4 == 3) {
         float *tr = a.trace + ((size_t)pr.row * a.out_ld + (pr.done + S) / 4) * pr.d;
 #pragma unroll
@@ -385,7 +358,6 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
         for (int e = 0; e < EPT; ++e)
             if (st.alive[e] && st.og[e] >= 0) tr[st.og[e]] = (float)st.w[e];
     }
-    OBC_TICK(6);   // records, trace
     return 0;
 }
 
@@ -468,7 +440,6 @@ __global__ __launch_bounds__(T) void panel_kernel(PanelArgs a)
     pr.qmax = (double)a.maxq;
     if (MODE == MODE_QUANT) { pr.qd = (double)a.delta[row]; pr.qo = (double)a.offset[row]; }
     pr.iqd = 1.0 / pr.qd;
-    pr.tick = __builtin_readcyclecounter();
     __syncthreads();
 
     bool failed = false;
@@ -514,6 +485,20 @@ __global__ __launch_bounds__(T) void panel_kernel(PanelArgs a)
 }
 
 
+// A kernel's dynamic LDS limit is a per-device attribute: `done` remembers, one bit per device, where
+// it has been raised for `fn`.  Safe from several host threads (raising it twice is harmless).
+inline int panel_raise_lds_limit(const void *fn, std::atomic<unsigned long long> &done)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return -1;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return 0;
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(160 * 1024 - 2048)) != hipSuccess)
+        return -1;
+    done.fetch_or(bit, std::memory_order_release);
+    return 0;
+}
+
 #define OBC_DEFINE_PANEL(T, EPT, BR, BL)                                                            \
     int launch_panel_##T##_##EPT##_##BR##_##BL(int mode, int R, size_t lds_nm, hipStream_t st,      \
                                                const PanelArgs &a)                                  \
@@ -521,13 +506,10 @@ __global__ __launch_bounds__(T) void panel_kernel(PanelArgs a)
         const size_t lds = (size_t)(BL) * (T) * (EPT) * sizeof(float) + lds_nm;                     \
         auto kp = panel_kernel<MODE_PRUNE, T, EPT, BR, BL>;                                         \
         auto kq = panel_kernel<MODE_QUANT, T, EPT, BR, BL>;                                         \
-        static bool attr_set = false;                                                               \
-        if (!attr_set && lds > 48 * 1024) {                                                         \
-            if (hipFuncSetAttribute((const void *)kp, hipFuncAttributeMaxDynamicSharedMemorySize,   \
-                                    (int)(160 * 1024 - 2048)) != hipSuccess) return -1;             \
-            if (hipFuncSetAttribute((const void *)kq, hipFuncAttributeMaxDynamicSharedMemorySize,   \
-                                    (int)(160 * 1024 - 2048)) != hipSuccess) return -1;             \
-            attr_set = true;                                                                        \
+        static std::atomic<unsigned long long> raised_p{0}, raised_q{0};                            \
+        if (lds > 48 * 1024) {                                                                      \
+            if (mode == MODE_PRUNE && panel_raise_lds_limit((const void *)kp, raised_p) != 0) return -1; \
+            if (mode != MODE_PRUNE && panel_raise_lds_limit((const void *)kq, raised_q) != 0) return -1; \
         }                                                                                           \
         if (mode == MODE_PRUNE) hipLaunchKernelGGL(kp, dim3(R), dim3(T), lds, st, a);               \
         else hipLaunchKernelGGL(kq, dim3(R), dim3(T), lds, st, a);                                  \
@@ -541,12 +523,8 @@ __global__ __launch_bounds__(T) void panel_kernel(PanelArgs a)
     {                                                                                               \
         const size_t lds = (size_t)(BL) * (T) * (EPT) * sizeof(float) + lds_nm;                     \
         auto kb = panel_kernel<MODE_BLOCK, T, EPT, BR, BL>;                                         \
-        static bool attr_set = false;                                                               \
-        if (!attr_set && lds > 48 * 1024) {                                                         \
-            if (hipFuncSetAttribute((const void *)kb, hipFuncAttributeMaxDynamicSharedMemorySize,   \
-                                    (int)(160 * 1024 - 2048)) != hipSuccess) return -1;             \
-            attr_set = true;                                                                        \
-        }                                                                                           \
+        static std::atomic<unsigned long long> raised{0};                                           \
+        if (lds > 48 * 1024 && panel_raise_lds_limit((const void *)kb, raised) != 0) return -1;     \
         hipLaunchKernelGGL(kb, dim3(R), dim3(T), lds, st, a);                                       \
         return 0;                                                                                   \
     }

@@ -45,7 +45,7 @@ struct BlockedWs {
     float *G;           // R x BMAX x ldu  rows of the matrix at the block's pivots
     double *Mb;         // R x BMAX x BMAX the pivots' principal submatrix, then its Cholesky factor
     double *Tb;         // R x BMAX x BMAX inverse of that factor
-    int *scal;          // [0] smallest number of up-front eliminations over the rows
+    int *scal;          // [0] smallest number of up-front eliminations over the rows, [1] the most eliminations any row does
 };
 
 

@@ -161,18 +161,28 @@ struct DeadArgs {
     BlockedWs ws;
 };
 
-__global__ __launch_bounds__(256) void min_ndead_kernel(const int *__restrict__ ndead, int R, int *out)
+// out[0] = smallest number of up-front eliminations over the rows, out[1] = largest number of
+// eliminations (up-front + greedy) any row does
+__global__ __launch_bounds__(256) void min_ndead_kernel(const int *__restrict__ ndead, const int *__restrict__ total,
+                                                        int R, int *out)
 {
-    __shared__ int red[256];
-    int v = 0x7fffffff;
-    for (int i = threadIdx.x; i < R; i += 256) v = ndead[i] < v ? ndead[i] : v;
+    __shared__ int red[256], redt[256];
+    int v = 0x7fffffff, t = 0;
+    for (int i = threadIdx.x; i < R; i += 256) {
+        v = ndead[i] < v ? ndead[i] : v;
+        t = total[i] > t ? total[i] : t;
+    }
     red[threadIdx.x] = v;
+    redt[threadIdx.x] = t;
     __syncthreads();
     for (int w = 128; w > 0; w >>= 1) {
-        if ((int)threadIdx.x < w) red[threadIdx.x] = red[threadIdx.x + w] < red[threadIdx.x] ? red[threadIdx.x + w] : red[threadIdx.x];
+        if ((int)threadIdx.x < w) {
+            red[threadIdx.x] = red[threadIdx.x + w] < red[threadIdx.x] ? red[threadIdx.x + w] : red[threadIdx.x];
+            redt[threadIdx.x] = redt[threadIdx.x + w] > redt[threadIdx.x] ? redt[threadIdx.x + w] : redt[threadIdx.x];
+        }
         __syncthreads();
     }
-    if (threadIdx.x == 0) out[0] = red[0];
+    if (threadIdx.x == 0) { out[0] = red[0]; out[1] = redt[0]; }
 }
 
 // The block's pivots (the first BMAX pruned indices in compact order), the rows of the matrix at
@@ -618,7 +628,7 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
     FlushArgs fa;
     fa.d = d; fa.R = R; fa.ws = bw;
 
-    const int host_total = (mode == MODE_QUANT || live) ? d : k_steps;   // upper bound over the rows
+    int host_total = (mode == MODE_QUANT || live) ? d : k_steps;   // upper bound over the rows
     const size_t lds_nm = nm_m > 0 ? obc_align_up((size_t)(d / nm_m), 16) : 0;
     const size_t mat_stride = obc_align_up((size_t)d * d, 4);   // floats between two rows' matrices
     int host_done = 0;
@@ -671,11 +681,13 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
     // ---- already-pruned indices, BMAX at a time, as long as every row has that many left.  The
     // smallest count over the rows is read back once (the only wait in this call).
     if (live && mode != MODE_BLOCK) {
-        int min_dead = 0;
-        min_ndead_kernel<<<1, 256, 0, st>>>(bw.ndead, R, bw.scal);
+        int scal[2] = {0, 0};
+        min_ndead_kernel<<<1, 256, 0, st>>>(bw.ndead, bw.total, R, bw.scal);
         OBC_LAUNCH_CHECK(ctx, "min_ndead_kernel");
-        OBC_HIP(ctx, hipMemcpyAsync(&min_dead, bw.scal, sizeof(int), hipMemcpyDeviceToHost, st));
+        OBC_HIP(ctx, hipMemcpyAsync(scal, bw.scal, sizeof(scal), hipMemcpyDeviceToHost, st));
         OBC_HIP(ctx, hipStreamSynchronize(st));
+        const int min_dead = scal[0];
+        if (scal[1] < host_total) host_total = scal[1];    // no launches past the longest row's last step
         int nfast = min_dead / BMAX;
         if (d - nfast * BMAX < BMAX) nfast -= 1;            // keep a matrix for the flush to write
         DeadArgs da;

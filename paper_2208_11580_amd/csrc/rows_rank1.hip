@@ -222,7 +222,7 @@ __global__ __launch_bounds__(1024) void rows_rank1_kernel(Rank1Args a)
             wp = w[p];
             double code = 0.0;
             if (MODE == MODE_QUANT) {
-                code = rint((wp - qo) / qd);
+                code = rint((wp - qo) * iqd);   // same expression as in the selection
                 code = fmin(fmax(code, 0.0), qmax);
                 target = qo + qd * code;
             }
@@ -305,6 +305,15 @@ __global__ __launch_bounds__(1024) void rows_rank1_kernel(Rank1Args a)
     }
 
     if (failed && tid == 0) obc_latch(a.status, OBC_ERR_NUMERIC);
+    // trace entries of the steps this row does not take are zero
+    if (a.trace) {
+        const int t0 = (steps < 0 ? 0 : steps) / bc;
+        const int t1 = (MODE == MODE_QUANT) ? t0 : a.k_steps;
+        for (int t = t0; t < t1; ++t) {
+            float *tr = a.trace + ((size_t)row * a.out_ld + t) * d;
+            for (int j = tid; j < d; j += nthr) tr[j] = 0.f;
+        }
+    }
     __syncthreads();
     for (int j = tid; j < d; j += nthr) a.W_out[(size_t)row * d + j] = (float)w[j];
 }

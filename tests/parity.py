@@ -165,3 +165,57 @@ def check_block_row(orc, Hinv32, w32, c, g_order, g_loss, g_w, k_blocks, g_trace
         num = np.linalg.norm(gt - r.trace, axis=1)
         assert np.all(num <= W_RTOL * np.linalg.norm(r.trace, axis=1) + 1e-30)
     return swapped
+
+
+def check_rows(orc, stats, mode, Hinv32, W32, g_order, g_loss, g_w, k_steps, nm=(0, 0), grids=None,
+               g_codes=None, n_threads=16):
+    """Several rows at once: the oracle's multi-row driver (one row per host thread) runs them
+    all; a row whose order and codes equal the GPU's is compared with that run directly, any other
+    row goes through check_row (forced replay, near-tie rule, rounding-boundary rule).
+
+    grids = (delta[rows], offset[rows], maxq) for mode "quant".  g_* hold the sampled rows only.
+    """
+    A = np.asarray(Hinv32, np.float64)
+    W = np.asarray(W32, np.float64)
+    n, d = W.shape
+    if mode == "prune":
+        ro = orc.prune_rows(A, W, k_steps=k_steps, nm=nm, n_threads=n_threads)
+    else:
+        assert k_steps == d
+        ro = orc.quant_rows(A, W, np.asarray(grids[0], np.float64), np.asarray(grids[1], np.float64), grids[2],
+                            n_threads=n_threads)
+    for i in range(n):
+        go = np.asarray(g_order[i][:k_steps], np.int64)
+        same = np.array_equal(go, ro["order"][i])
+        if same and mode == "quant" and g_codes is not None:
+            same = np.array_equal(np.asarray(g_codes[i]), ro["codes"][i])
+        if not same:
+            grid = None if mode == "prune" else (float(grids[0][i]), float(grids[1][i]), grids[2])
+            check_row(orc, stats, mode, Hinv32, W32[i], g_order[i], g_loss[i], g_w[i], k_steps, nm=nm, grid=grid,
+                      g_codes=None if g_codes is None else g_codes[i])
+            continue
+        stats.rows += 1
+        stats.steps += k_steps
+        gw = np.asarray(g_w[i], np.float64)
+        ref = ro["W"][i]
+        nrm, err = np.linalg.norm(ref), np.linalg.norm(gw - ref)
+        if nrm > 0:
+            stats.max_w_err = max(stats.max_w_err, err / nrm)
+            assert err <= W_RTOL * nrm, "row %d: weights differ: rel %.3e" % (i, err / nrm)
+        else:
+            assert err == 0.0
+        if mode == "prune":
+            assert np.all(gw[go] == 0.0), "pruned weights must be exactly zero"
+        gl = np.asarray(g_loss[i][:k_steps], np.float64)
+        tot = ro["loss"][i].sum()
+        if tot > 0:
+            e = abs(gl.sum() - tot) / tot
+            stats.max_loss_err = max(stats.max_loss_err, e)
+            assert e <= LOSS_RTOL, "row %d: accumulated loss differs: rel %.3e" % (i, e)
+        assert np.allclose(gl, ro["loss"][i], rtol=5e-3, atol=1e-6 * (np.max(ro["loss"][i]) if k_steps else 0.0))
+        if mode == "quant":
+            delta, offset, maxq = float(grids[0][i]), float(grids[1][i]), grids[2]
+            gc = np.asarray(g_codes[i])
+            deq = (np.float64(offset) + np.float64(delta) * gc.astype(np.float64)).astype(np.float32)
+            assert np.array_equal(gw.astype(np.float32), deq)
+    return ro

@@ -335,6 +335,43 @@ def test_quant_rows_matches_oracle(obc, orc, strategy, d, R, bits):
     _check_quant(obc, orc, W, Hinv, bits, strategy)
 
 
+@pytest.mark.parametrize("strategy", [1, 2])
+@pytest.mark.parametrize("d", [64, 320])
+def test_quant_rows_at_rounding_boundaries(obc, orc, strategy, d):
+    """Weights exactly on a half step of the grid, and one fp32 ulp to either side: the code written
+    is the code the candidate was scored with (round half to even), and both equal the oracle's.
+    The inverse Hessian is diagonal, so OBQ is plain rounding and every weight keeps its value
+    until it is chosen."""
+    delta, offset, maxq = 0.25, -1.0, 7          # the grid -1, -0.75, ..., 0.75; exact in fp32
+    base = np.float32(offset) + np.float32(delta) * (np.arange(d, dtype=np.float32) % 7 + np.float32(0.5))
+    rows = np.stack([base, np.nextafter(base, np.float32(-4), dtype=np.float32),
+                     np.nextafter(base, np.float32(4), dtype=np.float32)]).astype(np.float32)
+    rng = np.random.default_rng(5)
+    diag = rng.uniform(0.5, 2.0, d).astype(np.float32)
+    W = torch.tensor(rows, device="cuda")
+    Hinv = torch.diag(torch.tensor(diag, device="cuda")).contiguous()
+    dl = torch.full((3,), delta, device="cuda")
+    of = torch.full((3,), offset, device="cuda")
+    q = obc.obc_quant_rows(W, Hinv, dl, of, maxq, strategy=strategy)
+    obc.obc_check()
+    codes = _np(q["codes"])
+    for i in range(3):
+        want = np.array([orc.quant_code(float(rows[i, j]), delta, offset, maxq) for j in range(d)])
+        assert np.array_equal(codes[i], want), (i, np.flatnonzero(codes[i] != want)[:5])
+        ro = orc.quant_row(np.diag(diag.astype(np.float64)), rows[i].astype(np.float64), (delta, offset, maxq))
+        assert np.array_equal(codes[i], ro.codes)
+        # the recorded loss is the one of the written code
+        step_of = np.empty(d, np.int64)
+        step_of[_np(q["order"][i])] = np.arange(d)
+        err = (offset + delta * codes[i].astype(np.float64)) - rows[i].astype(np.float64)
+        assert np.allclose(_np(q["loss"][i])[step_of], err * err / (2.0 * diag.astype(np.float64)), rtol=1e-5, atol=1e-12)
+    # exactly on the half step the even code wins: 0.5 -> 0, 1.5 -> 2, 2.5 -> 2, ...
+    half = (np.arange(d) % 7) + 0.5
+    assert np.array_equal(codes[0], np.minimum(np.round(half), maxq).astype(np.int32))
+    deq = (of[:, None].double() + dl[:, None].double() * q["codes"].double()).float()
+    assert torch.equal(q["W"], deq)
+
+
 def _narrow_grid(W, bits, shrink):
     """A min-max grid shrunk about its centre: the weights beyond it start as outliers."""
     maxq = (1 << bits) - 1
