@@ -319,13 +319,17 @@ __device__ __forceinline__ int panel_step(const PanelArgs &a, const PanelRow &pr
     // ---- (3) bring the fetched row up to date, keep it, update w and the diagonal
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-        float c = col[e];
         int j = tid + e * T;
+        // the correction is summed on its own and subtracted once: its roundings are then relative
+        // to the (small) correction instead of to the matrix entry, and the sum does not wait for
+        // the fetched row
+        float corr = 0.f;
 #pragma unroll
         for (int r = 0; r < S; ++r) {
             float ur = (r < BR) ? st.u[r < BR ? r : 0][e] : ul[(r - BR) * CAP + j];
-            c = fmaf(-cv[r], ur, c);
+            corr = fmaf(cv[r], ur, corr);
         }
+        float c = __fsub_rn(col[e], corr);
         if constexpr (S < BR) st.u[S < BR ? S : 0][e] = c;
         else ul[(S - BR) * CAP + j] = c;
         if constexpr (MODE == MODE_BLOCK) {

@@ -339,8 +339,8 @@ struct FlushArgs {
 // wave, i.e. whole 128-byte lines) and stored straight to the new one.  Accesses to the matrices
 // are raw buffer loads / stores: a 32-bit byte offset per access instead of a 64-bit address
 // (register pressure), and the hardware range check (offset >= size reads 0 / drops the store)
-// replaces the per-element predicates.  The loads of the next tile are issued before the MFMAs
-// of the current one.
+// replaces the per-element predicates.  A tile's loads are issued before its MFMAs, which do not
+// depend on them.
 typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 constexpr unsigned kBufWord3 = 0x00020000u;   // raw buffer, 32-bit data format
 constexpr int kFar = 0x40000000;              // byte offset beyond any matrix: "out of range"
@@ -448,7 +448,6 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
             if (KMAX * (FT / 4) % 512 == 0 || k < KMAX) *reinterpret_cast<float4 *>(&Us[k][j]) = ureg[h];
         }
     };
-    floatx16 acc[2], nxt[2];
     // strictly-lower tiles: element (i, j) sits at old[map i][map j]; rb = first strip row of the tile
     auto fetch_c = [&](floatx16(&c)[2], int jold, int rb) {
         const int joldB = (jold < 0) ? kFar : swz ? jold * 16 : jold * 4;
@@ -495,33 +494,40 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         else fetch_c(c, jold, hf * FT);
     };
 
+    // Per tile: the loads of the old entries are issued first, the rank-K update is summed on the
+    // matrix cores into accumulators that start at zero while those loads are in flight, and the
+    // two are added once at the end.  (Summing into the loaded entries instead would round every
+    // one of the K partial sums at the magnitude of the matrix entry; this way the update, which is
+    // small next to the entry, is rounded at its own magnitude, and the entry takes one rounding
+    // per block.  The loads overlap with the same tile's MFMAs instead of the previous tile's.)
     int j0 = 0, hf = 0;
     int jold = old_col(jl);
     fetch_u(0);
     __syncthreads();                           // rowoff_s / rowold_s visible
-    fetch_tile(acc, jold, j0, hf);
     stash_u();
     __syncthreads();                           // Us and Fs visible
+    floatx16 old[2], sum[2];
     for (;;) {
+        fetch_tile(old, jold, j0, hf);
         int j0n = j0, hfn = hf;
         const bool more = advance(j0n, hfn);
         const bool new_col = more && j0n != j0;
-        if (more) {
-            if (new_col) {
-                fetch_u(j0n);
-                jold = old_col(j0n + jl);
-            }
-            fetch_tile(nxt, jold, j0n, hfn);
+        int joldn = jold;
+        if (new_col) {
+            fetch_u(j0n);
+            joldn = old_col(j0n + jl);
         }
         const int kl = lane >> 5, il = lane & 31;
         const int rb = hf * FT;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { sum[0][v] = 0.f; sum[1][v] = 0.f; }
 #pragma unroll
         for (int kk = 0; kk < nbp; kk += 2) {
             float a0 = Fs[kk + kl][rb + wm * 64 + il];
             float a1 = Fs[kk + kl][rb + wm * 64 + 32 + il];
             float b0 = Us[kk + kl][wn * 32 + il];
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1], 0, 0, 0);
+            sum[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, sum[0], 0, 0, 0);
+            sum[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, sum[1], 0, 0, 0);
         }
         // store: a lane's registers 4q .. 4q+3 are four consecutive rows of its column = one
         // 16-byte slot of the row-quad layout
@@ -535,8 +541,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                 const int qrow = i0 + rb + wm * 64 + mt * 32 + 8 * q + lrow;   // first row of the quad
                 const int quad = qrow >> 2;
                 if (on_diag && jcol > qrow + 3) continue;                   // wholly above the diagonal
-                uintx4 v4 = {__float_as_uint(acc[mt][4 * q]), __float_as_uint(acc[mt][4 * q + 1]),
-                             __float_as_uint(acc[mt][4 * q + 2]), __float_as_uint(acc[mt][4 * q + 3])};
+                uintx4 v4 = {__float_as_uint(__fadd_rn(old[mt][4 * q], sum[mt][4 * q])),
+                             __float_as_uint(__fadd_rn(old[mt][4 * q + 1], sum[mt][4 * q + 1])),
+                             __float_as_uint(__fadd_rn(old[mt][4 * q + 2], sum[mt][4 * q + 2])),
+                             __float_as_uint(__fadd_rn(old[mt][4 * q + 3], sum[mt][4 * q + 3]))};
                 __builtin_amdgcn_raw_buffer_store_b128(v4, rnew, quad * ldn * 16 + colB, 0, kMatStorePolicy);
             }
         if (!more) break;
@@ -545,10 +553,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
             stash_u();
             __syncthreads();                   // the new Us visible
         }
-        acc[0] = nxt[0];
-        acc[1] = nxt[1];
         j0 = j0n;
         hf = hfn;
+        jold = joldn;
     }
 }
 

@@ -42,6 +42,7 @@ def test_conv256x2304_obq4_sampled_rows(obc, orc):
     check_rows(orc, st, "quant", A, _np(W[rows]), order, loss, Wo, d,
                grids=(_np(delta[rows]), _np(offset[rows]), maxq), g_codes=codes)
     print(st)
+    st.assert_order_rule()
     assert st.rows == len(rows)
     # properties that hold for every row at any size
     c = res["codes"]
@@ -94,6 +95,7 @@ def test_ffn768x3072_prune_sampled_row(obc, orc):
     check_rows(orc, st, "prune", A, _np(W[rows]), _np(res["order"][rows]), _np(res["loss"][rows]),
                _np(res["W"][rows]), d)
     print(st)
+    st.assert_order_rule()
     assert st.rows == len(rows)
     for i in (77, 612):
         c = int(counts[i])
@@ -159,6 +161,7 @@ def test_compound_prune_then_quantize(obc, orc):
                   n_live, grid=(float(delta[i]), float(offset[i]), maxq), g_codes=_np(q["codes"][i]),
                   live=_np(live[i]))
     print(st)
+    st.assert_order_rule()
     assert torch.all(q["W"][mask.bool()] == 0) and torch.all(q["codes"][mask.bool()] == -1)
 
 
@@ -179,6 +182,7 @@ def test_rank1_strategy_at_full_width(obc, orc):
               grid=(float(delta[1]), float(offset[1]), maxq), g_codes=_np(q["codes"][1]))
     check_row(orc, st, "prune", A, _np(W[2]), _np(p["order"][2]), _np(p["loss"][2]), _np(p["W"][2]), d)
     print(st)
+    st.assert_order_rule()
     # the two strategies take the same decisions
     qb = obc.obc_quant_rows(W, Hinv, delta, offset, maxq, strategy=pkg.STRATEGY_BLOCKED)
     assert (q["order"] != qb["order"]).float().mean().item() < 0.002
@@ -249,6 +253,7 @@ def test_conv256x2304_sequential_obq_with_outlier_heuristic(obc, orc):
         check_row(orc, st, "quant", A, _np(Wr[i]), _np(res["order"][i]), _np(res["loss"][i]), _np(res["W"][i]), d,
                   grid=(float(delta[i]), float(offset[i]), maxq), g_codes=_np(res["codes"][i]), outlier=True)
     print(st)
+    st.assert_order_rule()
 
 
 def test_width_4608_first_blocks(obc, orc):
@@ -265,6 +270,7 @@ def test_width_4608_first_blocks(obc, orc):
     check_row(orc, st, "prune", _np(Hinv), _np(W[1]), _np(res["order"][1]), _np(res["loss"][1]),
               _np(res["W"][1]), k)
     print(st)
+    st.assert_order_rule()
     assert int((res["W"] == 0).sum()) == R * k
     # OBQ over the same width: every weight ends on its grid value, the trace of loss changes sums
     # to the quadratic form (checked in fp64 against H itself)
@@ -301,6 +307,7 @@ def test_width_4608_quantize_survivors(obc, orc):
     check_row(orc, st, "quant", _np(Hinv), _np(p["W"][i]), _np(q["order"][i]), _np(q["loss"][i]), _np(q["W"][i]), k,
               grid=(float(delta[i]), float(offset[i]), maxq), g_codes=_np(q["codes"][i]), live=_np(live[i]))
     print(st)
+    st.assert_order_rule()
     # every row: pruned weights stay zero with code -1, survivors sit on their grid
     assert torch.all(q["W"][live == 0] == 0) and torch.all(q["codes"][live == 0] == -1)
     c = q["codes"]
@@ -335,6 +342,7 @@ def test_width_3200_first_steps(obc, orc):
     check_row(orc, st, "prune", _np(Hinv), _np(W[0]), _np(res["order"][0]), _np(res["loss"][0]),
               _np(res["W"][0]), k)
     print(st)
+    st.assert_order_rule()
     assert int((res["W"] == 0).sum()) == 2 * k
 
 
@@ -366,6 +374,7 @@ def test_transformer_layers_on_768_features_full_size(obc, orc, name):
     ro = check_rows(orc, st, "prune", A, _np(W[rows]), _np(res["order"][rows]), _np(res["loss"][rows]),
                     _np(res["W"][rows]), d)
     print(name, "prune", st)
+    st.assert_order_rule()
     # Algorithm 2 on the GPU's traces equals the oracle's Algorithm 2 on the same traces
     co = orc.global_select(_np(res["loss"]).astype(np.float64), k)
     assert np.array_equal(_np(counts), co)
@@ -385,6 +394,7 @@ def test_transformer_layers_on_768_features_full_size(obc, orc, name):
     check_rows(orc, st, "quant", A, _np(W[rows]), _np(q["order"][rows]), _np(q["loss"][rows]), _np(q["W"][rows]), d,
                grids=(_np(delta[rows]), _np(offset[rows]), maxq), g_codes=_np(q["codes"][rows]))
     print(name, "obq4", st)
+    st.assert_order_rule()
     c = q["codes"]
     assert int(c.min()) >= 0 and int(c.max()) <= maxq
     deq = (offset[:, None].double() + delta[:, None].double() * c.double()).float()
@@ -439,4 +449,6 @@ def test_conv512x4608_every_panel_variant_and_compound(obc, orc):
             f.result()
     print("4608 full row:", st_p)
     print("4608 compound rows:", st_q)
+    st_p.assert_order_rule()
+    st_q.assert_order_rule()
     assert st_p.rows == 1 and st_q.rows == 4

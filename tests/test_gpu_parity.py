@@ -164,6 +164,7 @@ def _check_prune(obc, orc, W, Hinv, k_steps, nm, strategy, rows=None, want_trace
         check_row(orc, st, "prune", A, Wn[i], order[i], loss[i], Wo[i], order.shape[1], nm=nm,
                   g_trace=None if tr is None else tr[i])
     print(st)
+    st.assert_order_rule()
     return res, st
 
 
@@ -323,6 +324,7 @@ def _check_quant(obc, orc, W, Hinv, bits, strategy, live=None, rows=None, grid=N
                   grid=(float(dl[i]), float(of[i]), maxq), g_codes=codes[i],
                   live=None if lv is None else lv[i], outlier=outliers)
     print(st)
+    st.assert_order_rule()
     return res, st
 
 
@@ -530,6 +532,7 @@ def test_prune_rows_on_an_already_sparse_matrix(obc, orc, strategy):
         check_row(orc, st, "prune", A, W1[i], _np(second["order"][i]), _np(second["loss"][i]),
                   _np(second["W"][i]), k2, live=_np(live[i]), g_trace=_np(second["trace"][i]))
     print(st)
+    st.assert_order_rule()
     assert int((second["W"] == 0).sum()) == 4 * (k1 + k2)
     # continuing from the reduced inverse is continuing the same greedy run: the one-pass run over
     # k1 + k2 steps takes (up to near ties) the same weights next
