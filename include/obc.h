@@ -226,6 +226,21 @@ int obc_global_select_workspace_bytes(int R, int d, size_t *bytes);
 int obc_global_select(obc_ctx *ctx, const float *loss, const int32_t *order, int R, int d,
                       int64_t k, int32_t *counts, uint8_t *mask, void *ws, size_t ws_bytes);
 
+/* The same global step for callers that cannot allocate device memory or hand over a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid allocation): the
+ * scratch is a device array built into the library, OBC_SELECT_STATIC_SCRATCH_BYTES per GPU, held
+ * from the library's load to the end of the process.  Arguments, results and errors as
+ * obc_global_select; layers beyond OBC_SELECT_STATIC_MAX_WEIGHTS weights or
+ * OBC_SELECT_STATIC_MAX_ROWS rows are refused with OBC_ERR_WORKSPACE.  The call allocates and
+ * frees nothing, waits for nothing and clears its scratch with kernels.  All calls on one GPU
+ * share that GPU's array: calls that overlap in time on one GPU (two streams, two contexts) race;
+ * calls on one stream are ordered and safe. */
+#define OBC_SELECT_STATIC_MAX_WEIGHTS 2359296 /* R * d, e.g. 512 x 4608, 768 x 3072, 3072 x 768 */
+#define OBC_SELECT_STATIC_MAX_ROWS 8192
+#define OBC_SELECT_STATIC_SCRATCH_BYTES (4 * OBC_SELECT_STATIC_MAX_WEIGHTS + 2 * 4 * OBC_SELECT_STATIC_MAX_ROWS + 2048)
+int obc_global_select_static(obc_ctx *ctx, const float *loss, const int32_t *order, int R, int d,
+                             int64_t k, int32_t *counts, uint8_t *mask);
+
 /* ---- Sec. 4 Step 2: weights of the chosen mask from the pruning trace -------------------
  * W_out[i] = trace[i][counts[i]-1] (the row after counts[i] steps), or W[i] when counts[i] == 0.
  * trace is R x k_steps x d with k_steps >= max counts. */

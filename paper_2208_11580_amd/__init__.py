@@ -1,4 +1,5 @@
 """MI355X-native ExactOBS / OBQ layer solver (arxiv 2208.11580): libobc.so + its ctypes binding."""
+from . import binding  # noqa: F401
 from .binding import (  # noqa: F401
     Context, ObcError, load_library, LIB_PATH, EXPORTS,
     STRATEGY_AUTO, STRATEGY_RANK1, STRATEGY_BLOCKED,

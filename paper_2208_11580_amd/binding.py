@@ -21,6 +21,7 @@ OBC_ERR_BAD_ARG, OBC_ERR_BAD_SHAPE, OBC_ERR_NOT_SPD = -1, -2, -3
 OBC_ERR_WORKSPACE, OBC_ERR_NUMERIC, OBC_ERR_HIP = -4, -5, -6
 STRATEGY_AUTO, STRATEGY_RANK1, STRATEGY_BLOCKED = 0, 1, 2
 QUANT_OUTLIERS = 1
+SELECT_STATIC_MAX_WEIGHTS, SELECT_STATIC_MAX_ROWS = 2359296, 8192   # limits of obc_global_select_static
 
 EXPORTS = [
     "obc_create", "obc_destroy", "obc_last_error", "obc_version", "obc_check",
@@ -29,7 +30,7 @@ EXPORTS = [
     "obc_invert_workspace_bytes", "obc_invert",
     "obc_cross_workspace_bytes", "obc_cross", "obc_refit_workspace_bytes", "obc_refit",
     "obc_rows_workspace_bytes", "obc_prune_rows", "obc_blocks_workspace_bytes", "obc_prune_blocks", "obc_quant_rows", "obc_minmax_grid",
-    "obc_global_select_workspace_bytes", "obc_global_select", "obc_gather_trace",
+    "obc_global_select_workspace_bytes", "obc_global_select", "obc_global_select_static", "obc_gather_trace",
 ]
 
 
@@ -89,6 +90,7 @@ def load_library():
     lib.obc_refit.argtypes = [vp, vp, c_int, vp, c_int, vp, c_int, vp, c_size_t]
     lib.obc_global_select_workspace_bytes.argtypes = [c_int, c_int, sp]
     lib.obc_global_select.argtypes = [vp, vp, vp, c_int, c_int, c_int64, vp, vp, vp, c_size_t]
+    lib.obc_global_select_static.argtypes = [vp, vp, vp, c_int, c_int, c_int64, vp, vp]
     lib.obc_gather_trace.argtypes = [vp, vp, vp, vp, c_int, c_int, c_int, vp]
     for name in EXPORTS:
         fn = getattr(lib, name)
@@ -331,6 +333,13 @@ class Context:
         self._ck(self.lib.obc_global_select(self.h, _ptr(loss, torch.float32), _ptr(order, torch.int32), R, d,
                                             int(k), _ptr(counts), _ptr(mask), c_void_p(ws.data_ptr()),
                                             ws.numel()))
+        return counts, mask
+
+    def obc_global_select_static(self, loss, order, k, counts, mask):
+        """The global step on the library's built-in scratch; every buffer is the caller's."""
+        R, d = loss.shape
+        self._ck(self.lib.obc_global_select_static(self.h, _ptr(loss, torch.float32), _ptr(order, torch.int32), R, d,
+                                                   int(k), _ptr(counts, torch.int32), _ptr(mask, torch.uint8)))
         return counts, mask
 
     def obc_gather_trace(self, W, trace, counts):

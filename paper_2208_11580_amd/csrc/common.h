@@ -23,6 +23,7 @@ struct obc_ctx {
     hipStream_t stream;
     int device;
     int *d_status;      // device error latch: 0, or the first OBC_ERR_* a kernel saw
+    void *select_scratch;   // this device's copy of the built-in scratch of obc_global_select_static
     char err[512];
     bool profiling;
     std::vector<obc_timed> timed;
@@ -56,6 +57,9 @@ struct obc_scope {
         ctx->timed.push_back(t);
     }
 };
+
+// global_select.hip: device address of the built-in scratch array on `device` (the current device)
+int obc_select_scratch_address(int device, void **ptr);
 
 static inline int obc_fail(obc_ctx *ctx, int code, const char *fmt, ...)
 {

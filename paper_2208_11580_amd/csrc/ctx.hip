@@ -13,12 +13,14 @@ int obc_create(obc_ctx **out, void *hip_stream)
     if (!ctx) return OBC_ERR_BAD_ARG;
     ctx->stream = (hipStream_t)hip_stream;
     ctx->d_status = nullptr;
+    ctx->select_scratch = nullptr;
     ctx->err[0] = 0;
     ctx->device = 0;
     ctx->profiling = false;
     hipError_t e = hipGetDevice(&ctx->device);
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->d_status, 256);
     if (e == hipSuccess) e = hipMemsetAsync(ctx->d_status, 0, 256, ctx->stream);
+    if (e == hipSuccess && obc_select_scratch_address(ctx->device, &ctx->select_scratch) != OBC_OK) e = hipErrorUnknown;
     if (e != hipSuccess) {
         if (ctx->d_status) (void)hipFree(ctx->d_status);
         delete ctx;

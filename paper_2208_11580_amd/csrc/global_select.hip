@@ -14,6 +14,8 @@
 // passes, integer histograms) of the k-th smallest key value v; per row the counts of keys
 // < v and == v (keys are non-decreasing along a row, so those are prefixes); ties at v are
 // handed out in row order; finally the mask is scattered from the per-row pruning order.
+#include <mutex>
+
 #include "common.h"
 
 namespace {
@@ -198,6 +200,32 @@ __global__ void fill_i32_kernel(int *p, int n, int v)
 
 }  // namespace
 
+// ---- the variant that allocates nothing: its scratch region is a device array of this library.
+// Every GPU holds its own copy of the array at its own address; in host code the array's name is
+// only a handle for hipGetSymbolAddress, never a pointer to pass on.
+static __device__ __align__(256) unsigned char select_scratch[OBC_SELECT_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::mutex select_scratch_mutex;
+static void *select_scratch_ptr[kMaxDevices];   // device address of select_scratch on each device, once known
+
+// Device address of select_scratch on `device`, which must be the current device (obc_create
+// calls this, so a context always finds its device's entry filled).
+int obc_select_scratch_address(int device, void **ptr)
+{
+    if (device < 0 || device >= kMaxDevices || !ptr) return OBC_ERR_BAD_ARG;
+    std::lock_guard<std::mutex> lock(select_scratch_mutex);
+    if (!select_scratch_ptr[device]) {
+        int cur = -1;
+        if (hipGetDevice(&cur) != hipSuccess || cur != device) return OBC_ERR_HIP;
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(select_scratch)) != hipSuccess || !p) return OBC_ERR_HIP;
+        select_scratch_ptr[device] = p;
+    }
+    *ptr = select_scratch_ptr[device];
+    return OBC_OK;
+}
+
 extern "C" {
 
 int obc_global_select_workspace_bytes(int R, int d, size_t *bytes)
@@ -209,21 +237,11 @@ int obc_global_select_workspace_bytes(int R, int d, size_t *bytes)
     return OBC_OK;
 }
 
-int obc_global_select(obc_ctx *ctx, const float *loss, const int32_t *order, int R, int d, int64_t k,
-                      int32_t *counts, uint8_t *mask, void *ws, size_t ws_bytes)
+// The kernels of the global step on a scratch region laid out as obc_global_select_workspace_bytes
+// describes (the caller has checked the arguments and the region's size).
+static int global_select_enqueue(obc_ctx *ctx, const float *loss, const int32_t *order, int R, int d, int64_t k,
+                                 int32_t *counts, uint8_t *mask, void *ws)
 {
-    if (!ctx) return OBC_ERR_BAD_ARG;
-    if (!loss || !order || !counts || !mask)
-        return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_global_select: null argument");
-    if (R < 0 || d <= 0) return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_global_select: bad size");
-    if (k < 0 || k > (int64_t)R * d)
-        return obc_fail(ctx, OBC_ERR_BAD_SHAPE, "obc_global_select: k (%lld) outside [0, R*d]", (long long)k);
-    size_t need;
-    obc_global_select_workspace_bytes(R, d, &need);
-    if (!ws || ws_bytes < need)
-        return obc_fail(ctx, OBC_ERR_WORKSPACE, "obc_global_select: workspace of %zu bytes needed, %zu given", need, ws_bytes);
-    if (R == 0) return OBC_OK;
-
     hipStream_t st = ctx->stream;
     const int64_t n = (int64_t)R * d;
     char *base = (char *)ws;
@@ -255,6 +273,50 @@ int obc_global_select(obc_ctx *ctx, const float *loss, const int32_t *order, int
     scatter_mask_kernel<<<R, 256, 0, st>>>(order, counts, d, mask);
     OBC_LAUNCH_CHECK(ctx, "global select kernels");
     return OBC_OK;
+}
+
+static int global_select_check_args(obc_ctx *ctx, const char *who, const float *loss, const int32_t *order, int R,
+                                    int d, int64_t k, const int32_t *counts, const uint8_t *mask)
+{
+    if (!loss || !order || !counts || !mask) return obc_fail(ctx, OBC_ERR_BAD_ARG, "%s: null argument", who);
+    if (R < 0 || d <= 0) return obc_fail(ctx, OBC_ERR_BAD_ARG, "%s: bad size", who);
+    if (k < 0 || k > (int64_t)R * d)
+        return obc_fail(ctx, OBC_ERR_BAD_SHAPE, "%s: k (%lld) outside [0, R*d]", who, (long long)k);
+    return OBC_OK;
+}
+
+int obc_global_select(obc_ctx *ctx, const float *loss, const int32_t *order, int R, int d, int64_t k,
+                      int32_t *counts, uint8_t *mask, void *ws, size_t ws_bytes)
+{
+    if (!ctx) return OBC_ERR_BAD_ARG;
+    int rc = global_select_check_args(ctx, "obc_global_select", loss, order, R, d, k, counts, mask);
+    if (rc != OBC_OK) return rc;
+    size_t need;
+    obc_global_select_workspace_bytes(R, d, &need);
+    if (!ws || ws_bytes < need)
+        return obc_fail(ctx, OBC_ERR_WORKSPACE, "obc_global_select: workspace of %zu bytes needed, %zu given", need, ws_bytes);
+    if (R == 0) return OBC_OK;
+    return global_select_enqueue(ctx, loss, order, R, d, k, counts, mask, ws);
+}
+
+int obc_global_select_static(obc_ctx *ctx, const float *loss, const int32_t *order, int R, int d, int64_t k,
+                             int32_t *counts, uint8_t *mask)
+{
+    if (!ctx) return OBC_ERR_BAD_ARG;
+    int rc = global_select_check_args(ctx, "obc_global_select_static", loss, order, R, d, k, counts, mask);
+    if (rc != OBC_OK) return rc;
+    size_t need;
+    obc_global_select_workspace_bytes(R, d, &need);
+    if ((int64_t)R * d > (int64_t)OBC_SELECT_STATIC_MAX_WEIGHTS || R > OBC_SELECT_STATIC_MAX_ROWS ||
+        need > (size_t)OBC_SELECT_STATIC_SCRATCH_BYTES)
+        return obc_fail(ctx, OBC_ERR_WORKSPACE,
+                        "obc_global_select_static: %d x %d exceeds the built-in scratch (at most %d weights in at "
+                        "most %d rows); use obc_global_select with a workspace", R, d,
+                        OBC_SELECT_STATIC_MAX_WEIGHTS, OBC_SELECT_STATIC_MAX_ROWS);
+    if (!ctx->select_scratch)
+        return obc_fail(ctx, OBC_ERR_HIP, "obc_global_select_static: the scratch address is unknown on device %d", ctx->device);
+    if (R == 0) return OBC_OK;
+    return global_select_enqueue(ctx, loss, order, R, d, k, counts, mask, ctx->select_scratch);
 }
 
 }  // extern "C"

@@ -38,7 +38,9 @@ int main()
     EXPECT(obc_cross_workspace_bytes(0, 2304, 50000, &n) == OBC_ERR_BAD_ARG);
     EXPECT(obc_refit_workspace_bytes(576, 64, &n) == OBC_OK);
     EXPECT(obc_refit_workspace_bytes(576, 0, &n) == OBC_ERR_BAD_ARG);
-    EXPECT(obc_global_select_workspace_bytes(3072, 768, &n) == OBC_OK);
+    EXPECT(obc_global_select_workspace_bytes(3072, 768, &n) == OBC_OK && n <= (size_t)OBC_SELECT_STATIC_SCRATCH_BYTES);
+    EXPECT(obc_global_select_workspace_bytes(OBC_SELECT_STATIC_MAX_ROWS, OBC_SELECT_STATIC_MAX_WEIGHTS / OBC_SELECT_STATIC_MAX_ROWS, &n) == OBC_OK &&
+           n <= (size_t)OBC_SELECT_STATIC_SCRATCH_BYTES);
     EXPECT(obc_global_select_workspace_bytes(4, 0, &n) == OBC_ERR_BAD_ARG);
     // a null context is refused before anything else is looked at
     float f = 0.f;
@@ -60,6 +62,7 @@ int main()
     EXPECT(obc_quant_rows(nullptr, &f, &f, 1, 1, &f, &f, 15, nullptr, 0, &i32, &f, &i32, &f, 0, &f, 4) == OBC_ERR_BAD_ARG);
     EXPECT(obc_minmax_grid(nullptr, &f, nullptr, 1, 1, 15, 0, &f, &f) == OBC_ERR_BAD_ARG);
     EXPECT(obc_global_select(nullptr, &f, &i32, 1, 1, 0, &i32, &u8, &f, 4) == OBC_ERR_BAD_ARG);
+    EXPECT(obc_global_select_static(nullptr, &f, &i32, 1, 1, 0, &i32, &u8) == OBC_ERR_BAD_ARG);
     EXPECT(obc_gather_trace(nullptr, &f, &f, &i32, 1, 1, 1, &f) == OBC_ERR_BAD_ARG);
     std::puts("libobc host sanitizer run clean");
     return 0;

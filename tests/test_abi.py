@@ -71,6 +71,18 @@ def test_host_only_calls(lib):
     assert lib.obc_blocks_workspace_bytes(8, 576, 9, 0, ctypes.byref(n)) == -1
 
 
+def test_binding_constants_match_the_header():
+    from paper_2208_11580_amd import binding
+
+    text = open(os.path.join(ROOT, "include", "obc.h")).read()
+    defs = dict(re.findall(r"#define\s+(OBC_[A-Z0-9_]+)\s+\(?(-?\d+)\)?", text))
+    assert int(defs["OBC_SELECT_STATIC_MAX_WEIGHTS"]) == binding.SELECT_STATIC_MAX_WEIGHTS
+    assert int(defs["OBC_SELECT_STATIC_MAX_ROWS"]) == binding.SELECT_STATIC_MAX_ROWS
+    for name in ("OBC_ERR_BAD_ARG", "OBC_ERR_BAD_SHAPE", "OBC_ERR_NOT_SPD", "OBC_ERR_WORKSPACE", "OBC_ERR_NUMERIC",
+                 "OBC_ERR_HIP"):
+        assert int(defs[name]) == getattr(binding, name)
+
+
 def test_no_oracle_in_product_path():
     """The package never imports the oracle (the oracle is test infrastructure)."""
     pkg = os.path.join(ROOT, "paper_2208_11580_amd")
