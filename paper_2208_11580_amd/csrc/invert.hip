@@ -63,20 +63,26 @@ __device__ __forceinline__ double rsqrt_f64(double x)
 // and holds c(4 r + l / 16, l % 16) in accumulator register r).  The off-diagonal sub-blocks of
 // L^-1 then follow from  T_is = -T_ii sum_{s <= k < i} L_ik T_ks.
 //
-// Batched use (one block per matrix): block b works on A + b strideA and Linv + b strideL; err is
-// the code latched on a bad pivot.
-__global__ __launch_bounds__(64) void potrf_wave_kernel(double *__restrict__ A, int lda, int bs,
-                                                        double *__restrict__ Linv, int *status,
-                                                        int64_t strideA, int64_t strideL, int err)
+// LDS of one diagonal-block factorisation (doubles): the block, the inverse of its factor, one sub-block
+constexpr int PL = NB + 1;
+constexpr int SB = 16;                        // sub-block edge
+constexpr int POTRF_LDS = 2 * NB * PL + SB * (SB + 1);
+
+// The factorisation runs on ONE wavefront; its LDS accesses are ordered with this (all earlier LDS
+// operations of the wavefront are complete and none later is moved before it).
+__device__ __forceinline__ void wave_lds_sync()
 {
-    A += (int64_t)blockIdx.x * strideA;
-    Linv += (int64_t)blockIdx.x * strideL;
-    constexpr int PL = NB + 1;
-    constexpr int SB = 16;                    // sub-block edge
-    __shared__ double Ls[NB * PL];            // the block; becomes L (lower triangle)
-    __shared__ double Ts[NB * PL];            // L^-1
-    __shared__ double Xs[SB * (SB + 1)];
-    const int lane = threadIdx.x, l16 = lane & 15, lg = lane >> 4;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+}
+
+__device__ __forceinline__ void potrf_wave(double *__restrict__ A, int lda, int bs, double *__restrict__ Linv,
+                                           int *status, int err, double *lds)
+{
+    double *Ls = lds;                         // the block; becomes L (lower triangle)
+    double *Ts = lds + NB * PL;               // L^-1
+    double *Xs = lds + 2 * NB * PL;
+    const int lane = threadIdx.x & 63, l16 = lane & 15, lg = lane >> 4;
 #pragma unroll 4
     for (int i = 0; i < NB; ++i) {
         double v = (i == lane) ? 1.0 : 0.0;
@@ -84,7 +90,7 @@ __global__ __launch_bounds__(64) void potrf_wave_kernel(double *__restrict__ A, 
         Ls[i * PL + lane] = v;
         Ts[i * PL + lane] = 0.0;
     }
-    __syncthreads();
+    wave_lds_sync();
 
     bool bad = false;
 #pragma unroll
@@ -136,7 +142,7 @@ __global__ __launch_bounds__(64) void potrf_wave_kernel(double *__restrict__ A, 
                 Ts[(o + c) * PL + o + lane] = t[c];
             }
         }
-        __syncthreads();
+        wave_lds_sync();
         // ---- sub-blocks below: L_is = A_is T_ss^T
         doublex4 P[NB / SB];
 #pragma unroll
@@ -150,12 +156,12 @@ __global__ __launch_bounds__(64) void potrf_wave_kernel(double *__restrict__ A, 
             }
             P[ib] = acc;
         }
-        __syncthreads();
+        wave_lds_sync();
 #pragma unroll
         for (int ib = s + 1; ib < NB / SB; ++ib)
 #pragma unroll
             for (int r = 0; r < 4; ++r) Ls[(SB * ib + 4 * r + lg) * PL + o + l16] = P[ib][r];
-        __syncthreads();
+        wave_lds_sync();
         // ---- trailing sub-blocks: A_ij -= L_is L_js^T  (s < j <= i)
 #pragma unroll
         for (int ib = s + 1; ib < NB / SB; ++ib)
@@ -173,7 +179,7 @@ __global__ __launch_bounds__(64) void potrf_wave_kernel(double *__restrict__ A, 
 #pragma unroll
                 for (int r = 0; r < 4; ++r) Ls[(SB * ib + 4 * r + lg) * PL + SB * jb + l16] = acc[r];
             }
-        __syncthreads();
+        wave_lds_sync();
     }
     // ---- off-diagonal sub-blocks of T = L^-1, block column by block column, top to bottom
 #pragma unroll
@@ -191,7 +197,7 @@ __global__ __launch_bounds__(64) void potrf_wave_kernel(double *__restrict__ A, 
                 }
 #pragma unroll
             for (int r = 0; r < 4; ++r) Xs[(4 * r + lg) * (SB + 1) + l16] = x[r];
-            __syncthreads();
+            wave_lds_sync();
             doublex4 y = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
             for (int kc = 0; kc < SB / 4; ++kc) {
@@ -201,7 +207,7 @@ __global__ __launch_bounds__(64) void potrf_wave_kernel(double *__restrict__ A, 
             }
 #pragma unroll
             for (int r = 0; r < 4; ++r) Ts[(SB * ib + 4 * r + lg) * PL + SB * s + l16] = y[r];
-            __syncthreads();
+            wave_lds_sync();
         }
 #pragma unroll 4
     for (int i = 0; i < NB; ++i) {
@@ -209,6 +215,16 @@ __global__ __launch_bounds__(64) void potrf_wave_kernel(double *__restrict__ A, 
         Linv[i * NB + lane] = (lane <= i) ? Ts[i * PL + lane] : 0.0;
     }
     if (lane == 0 && bad) obc_latch(status, err);
+}
+
+// Batched use (one block per matrix): block b works on A + b strideA and Linv + b strideL; err is
+// the code latched on a bad pivot.
+__global__ __launch_bounds__(64) void potrf_wave_kernel(double *__restrict__ A, int lda, int bs,
+                                                        double *__restrict__ Linv, int *status,
+                                                        int64_t strideA, int64_t strideL, int err)
+{
+    __shared__ double lds[POTRF_LDS];
+    potrf_wave(A + (int64_t)blockIdx.x * strideA, lda, bs, Linv + (int64_t)blockIdx.x * strideL, status, err, lds);
 }
 
 // C (M x N, leading dimension ldc) = alpha * sum_k a(i,k) b(k,j) + beta * C, with
@@ -232,7 +248,9 @@ struct GemmArgs {
     float *out32;
 };
 
-__device__ __forceinline__ void gemm64_tile(const GemmArgs &g, int ti, int tj)
+constexpr int GEMM_LDS = 2 * GK * (NB + 1);   // doubles: the two operand slabs of a tile
+
+__device__ __forceinline__ void gemm64_tile(const GemmArgs &g, int ti, int tj, double *lds)
 {
     const int M = g.M, N = g.N, K = g.K;
     const double alpha = g.alpha, beta = g.beta;
@@ -243,8 +261,8 @@ __device__ __forceinline__ void gemm64_tile(const GemmArgs &g, int ti, int tj)
     float *out32 = g.out32;
     if (ti * NB >= M || tj * NB >= N) return;
     if (lower_only && tj > ti) return;
-    __shared__ double As[GK][NB + 1];
-    __shared__ double Bs[GK][NB + 1];
+    double(*As)[NB + 1] = reinterpret_cast<double(*)[NB + 1]>(lds);
+    double(*Bs)[NB + 1] = reinterpret_cast<double(*)[NB + 1]>(lds + GK * (NB + 1));
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;   // 2 x 2 waves, 32 x 32 outputs each (2 x 2 MFMA tiles)
@@ -336,14 +354,47 @@ __device__ __forceinline__ void gemm64_tile(const GemmArgs &g, int ti, int tj)
             }
 }
 
-__global__ __launch_bounds__(256) void gemm64_kernel(GemmArgs g) { gemm64_tile(g, blockIdx.y, blockIdx.x); }
+__global__ __launch_bounds__(256) void gemm64_kernel(GemmArgs g)
+{
+    __shared__ double lds[GEMM_LDS];
+    gemm64_tile(g, blockIdx.y, blockIdx.x, lds);
+}
 
 // Two independent products in one launch (blockIdx.z picks the problem): the small products of a
 // factorisation step are latency-bound, so pairing them halves the number of launches.
 __global__ __launch_bounds__(256) void gemm64_dual_kernel(GemmArgs g0, GemmArgs g1)
 {
-    if (blockIdx.z == 0) gemm64_tile(g0, blockIdx.y, blockIdx.x);
-    else gemm64_tile(g1, blockIdx.y, blockIdx.x);
+    __shared__ double lds[GEMM_LDS];
+    if (blockIdx.z == 0) gemm64_tile(g0, blockIdx.y, blockIdx.x, lds);
+    else gemm64_tile(g1, blockIdx.y, blockIdx.x, lds);
+}
+
+// The trailing update of a factorisation step (g0: A22 -= L21 L21^T, lower tiles) and the update of
+// Y below the step's block row (g1), with the NEXT step's diagonal block looked ahead: the workgroup
+// that updates tile (0, 0) of A22 -- the next diagonal block -- goes on to factor it and invert its
+// factor (one wavefront), while the other workgroups do the rest of the two updates.  The
+// factorisation of a diagonal block (about 35 us on one wavefront) is the longest item of a step; this
+// takes it off the stream's serial chain.  That workgroup is the first one dispatched.
+struct LookAhead {
+    double *Akk;     // tile (0, 0) of A22
+    int lda, bs;
+    double *Linv;    // NB x NB out
+    int *status;
+};
+
+__global__ __launch_bounds__(256) void trailing_lookahead_kernel(GemmArgs g0, GemmArgs g1, LookAhead la)
+{
+    // (the factorisation reuses the tile product's LDS: the two never overlap in time)
+    __shared__ double lds[POTRF_LDS > GEMM_LDS ? POTRF_LDS : GEMM_LDS];
+    if (blockIdx.z != 0) {
+        gemm64_tile(g1, blockIdx.y, blockIdx.x, lds);
+        return;
+    }
+    gemm64_tile(g0, blockIdx.y, blockIdx.x, lds);
+    if (blockIdx.x != 0 || blockIdx.y != 0) return;
+    __threadfence();                           // the tile's entries, written by four waves, ...
+    __syncthreads();                           // ... are read back by the first
+    if (threadIdx.x < 64) potrf_wave(la.Akk, la.lda, la.bs, la.Linv, la.status, OBC_ERR_NOT_SPD, lds);
 }
 
 // Y = identity (d x d)
@@ -408,9 +459,10 @@ int factor_inverse(obc_ctx *ctx, const float *H, int d, void *ws, double **Yout)
     };
 
     // 1 + 2. Cholesky A = L L^T and Y = L^-1 together, block column by block column.  Step kb:
-    //   potrf:    L_kk and its inverse
+    //   (L_kk and its inverse: by the previous step's launch B; the first block by a launch of its own)
     //   launch A: L21 = A21 Linv_kk^T   |  Y[kb] = Linv_kk Y[kb]
     //   launch B: A22 -= L21 L21^T (lower tiles)  |  Y[rows below] -= L21 Y[kb]
+    //             | the next diagonal block, once updated, is factored and its factor inverted
     // (Y starts as the identity: forward substitution on the identity, right-looking; before step
     // kb its block row kb holds I_kb - sum_{j<kb} L[kb,j] Y[j], non-zero only in columns < k0 + bs.)
     for (int kb = 0; kb < nblk; ++kb) {
@@ -421,7 +473,7 @@ int factor_inverse(obc_ctx *ctx, const float *H, int d, void *ws, double **Yout)
         double *Akk = A + (int64_t)k0 * d + k0;
         double *Lk = Lb + (int64_t)kb * NB * NB;
         double *Yk = Y + (int64_t)k0 * d;
-        potrf_wave_kernel<<<1, 64, 0, st>>>(Akk, d, bs, Lk, ctx->d_status, 0, 0, OBC_ERR_NOT_SPD);
+        if (kb == 0) potrf_wave_kernel<<<1, 64, 0, st>>>(Akk, d, bs, Lk, ctx->d_status, 0, 0, OBC_ERR_NOT_SPD);
         // each workgroup overwrites exactly the rows / columns it has read
         GemmArgs trsm_row = mk(bs, nc, bs, 1.0, Lk, NB, 1, Yk, d, 1, 0.0, Yk, d, 0, 0, nullptr);
         if (m > 0) {
@@ -431,7 +483,10 @@ int factor_inverse(obc_ctx *ctx, const float *H, int d, void *ws, double **Yout)
             gemm64_dual_kernel<<<dual_grid(panel, trsm_row), 256, 0, st>>>(panel, trsm_row);
             GemmArgs trail = mk(m, m, bs, -1.0, A21, d, 1, A21, 1, d, 1.0, A22, d, 1, 0, nullptr);
             GemmArgs trsm_upd = mk(m, nc, bs, -1.0, A21, d, 1, Yk, d, 1, 1.0, Y + (int64_t)(k0 + bs) * d, d, 0, 0, nullptr);
-            gemm64_dual_kernel<<<dual_grid(trail, trsm_upd), 256, 0, st>>>(trail, trsm_upd);
+            LookAhead la;
+            la.Akk = A22; la.lda = d; la.bs = (m < NB) ? m : NB; la.Linv = Lk + (int64_t)NB * NB;
+            la.status = ctx->d_status;
+            trailing_lookahead_kernel<<<dual_grid(trail, trsm_upd), 256, 0, st>>>(trail, trsm_upd, la);
         } else {
             gemm64_kernel<<<grid64(bs, nc), 256, 0, st>>>(trsm_row);
         }
