@@ -177,6 +177,8 @@ def run_workload(ctx, pkg, workload, steps, warmup, strategy):
     # around each of its launches during the timed steps.  Algorithmic bytes / flops per launch are
     # those of the schedule the kernel implements (see include/obc.h, obc_profile_end).
     rows_s = 1e-3 * float(np.mean(stage_ms["rows"]))
+    if task.startswith("compound"):      # the second row-solver pass (OBQ on the survivors) sits in the last stage
+        rows_s += 1e-3 * float(np.mean(stage_ms["global"]))
     kern = {k: v for k, v in kstats.items() if v["launches"] > 0}
     dom = max(kern, key=lambda k: kern[k]["ms"])
     ds = kern[dom]
