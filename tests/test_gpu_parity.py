@@ -598,6 +598,48 @@ def test_rows_that_do_no_step_keep_their_weights(obc, strategy):
     assert torch.equal(none["W"], W)
 
 
+@pytest.mark.parametrize("strategy", [1, 2])
+def test_trace_beyond_a_rows_last_step_is_zero(obc, strategy):
+    """Trace entries of the steps a row does not take (per-row step limits, fewer survivors than
+    steps) are zero in both solvers, whatever the buffer held before."""
+    W, X = _layer("conv64x576", d_col=264, d_row=4, n_samples=1500)
+    Hinv = _hinv(obc, X)
+    k = 100
+    counts = torch.tensor([0, 7, 100, 64], dtype=torch.int32, device="cuda")
+    out = dict(trace=torch.full((4, k, 264), float("nan"), device="cuda"))
+    res = obc.obc_prune_rows(W, Hinv, k_steps=k, stop_counts=counts, strategy=strategy, out=out)
+    full = obc.obc_prune_rows(W, Hinv, k_steps=k, strategy=strategy, want_trace=True)
+    obc.obc_check()
+    for i, c in enumerate(counts.tolist()):
+        assert torch.equal(res["trace"][i, :c], full["trace"][i, :c])
+        assert torch.all(res["trace"][i, c:] == 0)
+    # an already sparse row runs out of survivors before k steps
+    live = torch.ones(4, 264, dtype=torch.uint8, device="cuda")
+    live[1, 40:] = 0                                           # 40 survivors
+    out = dict(trace=torch.full((4, k, 264), float("nan"), device="cuda"))
+    sp = obc.obc_prune_rows(W * live, Hinv, k_steps=k, live=live, strategy=strategy, out=out)
+    obc.obc_check()
+    assert torch.isfinite(sp["trace"]).all()
+    assert torch.all(sp["trace"][1, 40:] == 0)
+    assert torch.all(sp["trace"][1, 39] == 0) and not torch.all(sp["trace"][1, 38] == 0)
+
+
+def test_membench_kernels_move_what_they_say(obc):
+    """The plain copy kernel copies (both store policies); read and write passes return a time."""
+    n = 1 << 22
+    src = (torch.arange(n, device="cuda", dtype=torch.int32) * 2).view(torch.uint8)    # low bits clear
+    dst = torch.zeros_like(src)
+    for streaming in (False, True):
+        dst.zero_()
+        ms = obc.obc_membench(2, src, dst, src.numel(), reps=2, streaming=streaming)
+        assert ms > 0 and torch.equal(dst, src)
+    assert obc.obc_membench(0, src, None, src.numel(), reps=2) > 0
+    assert obc.obc_membench(1, None, dst, dst.numel(), reps=2, streaming=True) > 0
+    import paper_2208_11580_amd as pkg
+    with pytest.raises(pkg.ObcError):
+        obc.obc_membench(2, src, dst, 24, reps=1)              # not a multiple of 16 bytes
+
+
 def test_trace_of_an_odd_width_is_fully_written(obc, orc):
     # the trace is cleared by a 16-byte-wide fill before the steps scatter into it: a size that is
     # no multiple of four floats, over memory that held NaNs before
