@@ -13,6 +13,7 @@ What each function follows in the paper (arxiv 2208.11580):
 * ``quant_row(s)``    Sec. 5 eq. (7) / Appendix Algorithm 3
 * ``global_select``   Appendix Algorithm 2
 * ``reconstruct``     Sec. 4 Step 2: a row's weights depend only on how many of its weights were pruned
+* ``reconstruct_closed_form``  Sec. 4 Step 2: the group-OBS formula for all pruned weights of a row at once
 * ``compound_row``    Sec. 6 "Experimental Setup": prune first, then quantize the remaining weights,
                       on the dense sub-problem of the non-zeros (Sec. 4 "Implementation Details")
 """
@@ -339,6 +340,28 @@ def reconstruct(Hinv, W, counts):
     out = np.zeros_like(W)
     for i in range(W.shape[0]):
         out[i] = prune_row(Hinv, W[i], k_steps=int(counts[i])).w
+    return out
+
+
+def reconstruct_closed_form(Hinv, W, mask):
+    """Weights of every row for a given mask by the group-OBS formula of Sec. 4 Step 2 (its sign as in
+    eq. (5)): with P the pruned indices of the row,
+
+        w_hat = w - H^-1[:, P] ((H^-1)[P, P])^-1 w_P,      w_hat[P] = 0 exactly,
+
+    from the original weights and the original inverse Hessian.  The linear system is solved by the
+    library routine.  ``mask`` is R x d, non-zero = pruned.
+    """
+    A = np.asarray(Hinv, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    out = W.copy()
+    for i in range(W.shape[0]):
+        P = np.flatnonzero(np.asarray(mask[i]) != 0)
+        if P.size == 0:
+            continue
+        z = np.linalg.solve(A[np.ix_(P, P)], W[i, P])
+        out[i] = W[i] - A[:, P] @ z
+        out[i, P] = 0.0
     return out
 
 

@@ -754,3 +754,35 @@ def test_layer_error_equals_accumulated_loss_changes_without_dampening(orc):
     grids = [orc.minmax_grid(W[i], 3) for i in range(W.shape[0])]
     q = orc.quant_rows(A, W, [g[0] for g in grids], [g[1] for g in grids], grids[0][2])
     assert np.isclose(orc.layer_error(W, q["W"], X), q["loss"].sum(), rtol=1e-8)
+
+
+# ----------------------------------------------------------------------------- group-OBS recovery
+def test_closed_form_recovery_is_least_squares_on_the_support_and_the_replayed_state(orc):
+    """Sec. 4 Step 2: the weights for a mask follow from the group-OBS formula at once.  Pinned by
+    the least-squares problem on the kept support solved on H itself (never touching H^-1), by the
+    state Algorithm 1 reaches after pruning the same weights one by one, and by a two-weight case
+    worked out by hand."""
+    W, X = _problem(81, 20, n=90, R=3)
+    H = orc.hessian(X)
+    A = orc.invert(H)
+    res = orc.prune_rows(A, W, k_steps=20)
+    counts = np.array([0, 7, 20], np.int32)
+    mask = orc.mask_from_counts(res["order"], counts, 20)
+    got = orc.reconstruct_closed_form(A, W, mask)
+    assert np.array_equal(got[0], W[0])                       # nothing pruned: untouched
+    for i in range(3):
+        P = np.flatnonzero(mask[i])
+        ref = _ls_on_support(H, W[i], P, np.zeros(len(P)))
+        assert np.allclose(got[i], ref, rtol=1e-7, atol=1e-10)
+        assert np.all(got[i][P] == 0.0)
+    assert np.allclose(got, orc.reconstruct(A, W, counts), rtol=1e-7, atol=1e-10)
+    # a mask that no greedy run produced is handled alike
+    rng = np.random.default_rng(82)
+    m2 = (rng.random((3, 20)) < 0.4).astype(np.uint8)
+    got = orc.reconstruct_closed_form(A, W, m2)
+    for i in range(3):
+        P = np.flatnonzero(m2[i])
+        assert np.allclose(got[i], _ls_on_support(H, W[i], P, np.zeros(len(P))), rtol=1e-7, atol=1e-10)
+    # by hand: H^-1 = [[2, 1], [1, 1]], w = (3, 5), prune index 0: w1 - (1/2) * 3 = 3.5
+    out = orc.reconstruct_closed_form(np.array([[2.0, 1.0], [1.0, 1.0]]), np.array([[3.0, 5.0]]), np.array([[1, 0]]))
+    assert np.array_equal(out, np.array([[0.0, 3.5]]))
