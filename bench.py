@@ -53,7 +53,7 @@ BC = 4                                      # block size of the block-pruning wo
 NAMES = {"flush": "flush_kernel", "panel": "panel_kernel", "rank1": "rows_rank1_kernel"}
 
 
-def run_workload(ctx, pkg, workload, steps, warmup, strategy):
+def run_workload(ctx, pkg, workload, steps, warmup, strategy, recover="auto"):
     """Time `steps` passes of the whole path on one layer; returns the figures and what the oracle leg needs."""
     import numpy as np
     import torch
@@ -100,8 +100,8 @@ def run_workload(ctx, pkg, workload, steps, warmup, strategy):
                     W=torch.empty(R, d, device="cuda"), codes=torch.empty(R, d, dtype=torch.int32, device="cuda"))
     want_trace = task.startswith("prune") or task.startswith("compound") or task.startswith("block")
     trace_bytes = R * k_steps * d * 4
-    if want_trace and trace_bytes > 120e9:
-        want_trace = False        # largest layers: recover by replay instead of the HBM trace
+    if want_trace and (trace_bytes > 120e9 or recover in ("closed", "replay")):
+        want_trace = False        # largest layers (or on request): recover without the HBM trace
     if want_trace:
         out["trace"] = torch.empty(R, k_steps, d, device="cuda")
     ctx.workspace(max(ctx.rows_workspace_bytes(R, d, strategy), 1 << 20))
@@ -147,6 +147,9 @@ def run_workload(ctx, pkg, workload, steps, warmup, strategy):
             counts, mask = ctx.obc_global_select(res["loss"], res["order"], k)
             if want_trace:
                 result = ctx.obc_gather_trace(W, res["trace"], counts)
+            elif recover == "closed":
+                # group-OBS closed form on the mask; the largest per-row count sizes its workspace
+                result = ctx.obc_reconstruct_rows(W, H, mask, max_pruned=int(counts.max()))
             else:
                 result = ctx.obc_prune_rows(W, H, k_steps=k_steps, stop_counts=counts, strategy=strategy)["W"]
             if task.startswith("compound"):
@@ -316,6 +319,9 @@ def main():
     ap.add_argument("--no-second-layer", action="store_true",
                     help="skip the 768 x 3072 layer that the default run times after the headline workload")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows in the oracle sample (0 = one per host thread)")
+    ap.add_argument("--recover", default="auto", choices=["auto", "trace", "closed", "replay"],
+                    help="pruning workloads: how the weights of the global step's mask are recovered (auto: from the "
+                         "HBM trace when it fits, else by replay; closed: the group-OBS closed form)")
     ap.add_argument("--membench", action="store_true", help="time the plain read / write / copy kernels and exit")
     ap.add_argument("--calib-copy", action="store_true",
                     help="after the timed region run one plain 1 GiB device copy (calibrates rocprofv3's "
@@ -336,7 +342,7 @@ def main():
         membench(ctx)
         return
     strategy = {"auto": pkg.STRATEGY_AUTO, "rank1": pkg.STRATEGY_RANK1, "blocked": pkg.STRATEGY_BLOCKED}[args.strategy]
-    r = run_workload(ctx, pkg, args.workload, args.steps, args.warmup, strategy)
+    r = run_workload(ctx, pkg, args.workload, args.steps, args.warmup, strategy, args.recover)
     if args.calib_copy:
         nb = 1 << 30                                   # 1 GiB read, 1 GiB written
         src = torch.zeros(nb, dtype=torch.uint8, device="cuda")
@@ -350,7 +356,7 @@ def main():
         "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "d_row": r["R"], "d_col": r["d"], "n_samples": r["N"], "task": r["task"],
-                   "strategy": args.strategy, "row_steps": r["row_steps"]},
+                   "strategy": args.strategy, "row_steps": r["row_steps"], "recover": args.recover},
         "stages_ms": r["stages_ms"],
         "hessian_mfma_frac": r["hessian_mfma_frac"],
         "roofline": r["roofline"],

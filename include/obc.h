@@ -8,7 +8,8 @@
  *
  *     X --obc_hessian--> H = 2 X X^T + lambda I --obc_invert--> H^-1
  *       --obc_prune_rows / obc_quant_rows--> per-row order P, loss changes L, weights
- *       --obc_global_select--> per-row counts and layer mask --obc_gather_trace--> W^
+ *       --obc_global_select--> per-row counts and layer mask
+ *       --obc_gather_trace (from the pruning trace) or obc_reconstruct_rows (closed form)--> W^
  *
  * Conventions
  *  - Every array argument is a DEVICE pointer owned by the caller, row-major and
@@ -40,7 +41,7 @@ extern "C" {
 #define OBC_ERR_BAD_ARG (-1)   /* null pointer, negative size, value out of range */
 #define OBC_ERR_BAD_SHAPE (-2) /* sizes inconsistent with each other (d % M != 0, k > d, ...) */
 #define OBC_ERR_NOT_SPD (-3)   /* obc_invert met a non-positive Cholesky pivot */
-#define OBC_ERR_WORKSPACE (-4) /* workspace missing or smaller than the query says */
+#define OBC_ERR_WORKSPACE (-4) /* workspace missing or smaller than the query says (or than a row needs) */
 #define OBC_ERR_NUMERIC (-5)   /* a row solver met a non-positive / non-finite [H^-1]_pp */
 #define OBC_ERR_HIP (-6)       /* a HIP runtime call failed */
 
@@ -246,6 +247,22 @@ int obc_global_select_static(obc_ctx *ctx, const float *loss, const int32_t *ord
  * trace is R x k_steps x d with k_steps >= max counts. */
 int obc_gather_trace(obc_ctx *ctx, const float *W, const float *trace, const int32_t *counts,
                      int R, int d, int k_steps, float *W_out);
+
+/* ---- Sec. 4 Step 2: weights of a mask by the group-OBS closed form ------------------------
+ * For every row, with P the indices the mask marks as pruned,
+ *     W_out = w - H^-1[:, P] ((H^-1)[P, P])^-1 w_P,    W_out[P] = 0 exactly
+ * (the sign as in eq. (5)), from the ORIGINAL weights W and inverse Hessian Hinv: neither a trace nor a
+ * second run of the greedy loop is needed (the paper's cheaper way to a row's weights once the global
+ * step has fixed its mask).  The solve runs in fp64 through a Cholesky factorisation per row.
+ *   mask        R x d uint8, non-zero = pruned (as obc_global_select writes it)
+ *   max_pruned  upper bound on the pruned weights of any row, 0 <= max_pruned <= d; it sizes the
+ *               workspace (8 max_pruned^2 bytes per row, roughly).  A row with more pruned weights
+ *               than that is returned unchanged (a copy of W) and OBC_ERR_WORKSPACE is latched for
+ *               obc_check; a non-positive pivot latches OBC_ERR_NUMERIC.
+ * Asynchronous. */
+int obc_reconstruct_workspace_bytes(int R, int d, int max_pruned, size_t *bytes);
+int obc_reconstruct_rows(obc_ctx *ctx, const float *W, const float *Hinv, const uint8_t *mask, int R, int d,
+                         int max_pruned, float *W_out, void *ws, size_t ws_bytes);
 
 #ifdef __cplusplus
 }

@@ -31,6 +31,7 @@ EXPORTS = [
     "obc_cross_workspace_bytes", "obc_cross", "obc_refit_workspace_bytes", "obc_refit",
     "obc_rows_workspace_bytes", "obc_prune_rows", "obc_blocks_workspace_bytes", "obc_prune_blocks", "obc_quant_rows", "obc_minmax_grid",
     "obc_global_select_workspace_bytes", "obc_global_select", "obc_global_select_static", "obc_gather_trace",
+    "obc_reconstruct_workspace_bytes", "obc_reconstruct_rows",
 ]
 
 
@@ -92,6 +93,8 @@ def load_library():
     lib.obc_global_select.argtypes = [vp, vp, vp, c_int, c_int, c_int64, vp, vp, vp, c_size_t]
     lib.obc_global_select_static.argtypes = [vp, vp, vp, c_int, c_int, c_int64, vp, vp]
     lib.obc_gather_trace.argtypes = [vp, vp, vp, vp, c_int, c_int, c_int, vp]
+    lib.obc_reconstruct_workspace_bytes.argtypes = [c_int, c_int, c_int, sp]
+    lib.obc_reconstruct_rows.argtypes = [vp, vp, vp, vp, c_int, c_int, c_int, vp, vp, c_size_t]
     for name in EXPORTS:
         fn = getattr(lib, name)
         if name not in ("obc_last_error", "obc_version"):
@@ -347,4 +350,21 @@ class Context:
         W_out = torch.empty((R, d), dtype=torch.float32, device=W.device)
         self._ck(self.lib.obc_gather_trace(self.h, _ptr(W, torch.float32), _ptr(trace, torch.float32),
                                            _ptr(counts, torch.int32), R, d, k_steps, _ptr(W_out)))
+        return W_out
+
+    def obc_reconstruct_rows(self, W, Hinv, mask, max_pruned=None, W_out=None):
+        """Weights of a mask by the closed form; max_pruned bounds any row's pruned count (default: d)."""
+        R, d = W.shape
+        if max_pruned is None:
+            max_pruned = d
+        if W_out is None:
+            W_out = torch.empty((R, d), dtype=torch.float32, device=W.device)
+        need = c_size_t()
+        rc = self.lib.obc_reconstruct_workspace_bytes(R, d, int(max_pruned), byref(need))
+        if rc != OBC_OK:
+            raise ObcError(rc, "obc_reconstruct_workspace_bytes")
+        ws = self.workspace(need.value)
+        self._ck(self.lib.obc_reconstruct_rows(self.h, _ptr(W, torch.float32), _ptr(Hinv, torch.float32),
+                                               _ptr(mask, torch.uint8), R, d, int(max_pruned), _ptr(W_out),
+                                               c_void_p(ws.data_ptr()), ws.numel()))
         return W_out

@@ -322,7 +322,7 @@ __device__ __forceinline__ void gemm64_tile(const GemmArgs &g, int ti, int tj, d
             }
 }
 
-inline GemmArgs mk(int M, int N, int K, double alpha, const double *A, int64_t as_i, int64_t as_k, const double *B,
+__host__ __device__ inline GemmArgs mk(int M, int N, int K, double alpha, const double *A, int64_t as_i, int64_t as_k, const double *B,
             int64_t bs_k, int64_t bs_j, double beta, double *C, int64_t ldc, int lower_only, int klo_mode,
             float *out32)
 {

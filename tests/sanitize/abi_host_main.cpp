@@ -42,6 +42,9 @@ int main()
     EXPECT(obc_global_select_workspace_bytes(OBC_SELECT_STATIC_MAX_ROWS, OBC_SELECT_STATIC_MAX_WEIGHTS / OBC_SELECT_STATIC_MAX_ROWS, &n) == OBC_OK &&
            n <= (size_t)OBC_SELECT_STATIC_SCRATCH_BYTES);
     EXPECT(obc_global_select_workspace_bytes(4, 0, &n) == OBC_ERR_BAD_ARG);
+    EXPECT(obc_reconstruct_workspace_bytes(256, 2304, 1152, &n) == OBC_OK && n >= (size_t)256 * 1152 * 1152 * 8);
+    EXPECT(obc_reconstruct_workspace_bytes(4, 32, 0, &n) == OBC_OK);
+    EXPECT(obc_reconstruct_workspace_bytes(4, 32, 33, &n) == OBC_ERR_BAD_ARG);
     // a null context is refused before anything else is looked at
     float f = 0.f;
     int32_t i32 = 0;
@@ -64,6 +67,7 @@ int main()
     EXPECT(obc_global_select(nullptr, &f, &i32, 1, 1, 0, &i32, &u8, &f, 4) == OBC_ERR_BAD_ARG);
     EXPECT(obc_global_select_static(nullptr, &f, &i32, 1, 1, 0, &i32, &u8) == OBC_ERR_BAD_ARG);
     EXPECT(obc_gather_trace(nullptr, &f, &f, &i32, 1, 1, 1, &f) == OBC_ERR_BAD_ARG);
+    EXPECT(obc_reconstruct_rows(nullptr, &f, &f, &u8, 1, 1, 1, &f, &f, 4) == OBC_ERR_BAD_ARG);
     std::puts("libobc host sanitizer run clean");
     return 0;
 }

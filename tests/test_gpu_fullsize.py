@@ -452,3 +452,30 @@ def test_conv512x4608_every_panel_variant_and_compound(obc, orc):
     st_p.assert_order_rule()
     st_q.assert_order_rule()
     assert st_p.rows == 1 and st_q.rows == 4
+
+
+def test_conv256x2304_closed_form_recovery(obc, orc):
+    """The group-OBS closed form at full size: the 256 x 2304 layer pruned to 50 % by the global step;
+    every row's recovered weights against the weights gathered from the trace, sampled rows against
+    the oracle's closed form."""
+    W, X, _ = obc_inputs.make_layer("conv256x2304", device="cuda")
+    R, d = W.shape
+    Hinv = obc.obc_invert(obc.obc_hessian(X))
+    del X
+    res = obc.obc_prune_rows(W, Hinv, want_trace=True)
+    k = obc_inputs.target_count(0.5, R, d)
+    counts, mask = obc.obc_global_select(res["loss"], res["order"], k)
+    from_trace = obc.obc_gather_trace(W, res["trace"], counts)
+    del res
+    got = obc.obc_reconstruct_rows(W, Hinv, mask, max_pruned=int(counts.max()))
+    obc.obc_check()
+    assert torch.equal(got == 0, mask.bool())
+    num = (got.double() - from_trace.double()).norm(dim=1)
+    den = from_trace.double().norm(dim=1)
+    print("closed form vs trace, worst row: rel %.2e" % float((num / den).max()))
+    assert torch.all(num <= 1e-4 * den)
+    rows = [0, 100, 255]
+    ref = orc.reconstruct_closed_form(_np(Hinv), _np(W[rows]), _np(mask[rows]))
+    g = _np(got[rows]).astype(np.float64)
+    for n in range(len(rows)):
+        assert np.linalg.norm(g[n] - ref[n]) <= 1e-6 * np.linalg.norm(ref[n])
