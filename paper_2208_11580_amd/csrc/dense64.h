@@ -61,12 +61,22 @@ __device__ __forceinline__ void potrf_wave(double *__restrict__ A, int lda, int 
     double *Ts = lds + NB * PL;               // L^-1
     double *Xs = lds + 2 * NB * PL;
     const int lane = threadIdx.x & 63, l16 = lane & 15, lg = lane >> 4;
-#pragma unroll 4
-    for (int i = 0; i < NB; ++i) {
-        double v = (i == lane) ? 1.0 : 0.0;
-        if (i < bs && lane <= i) v = A[(int64_t)i * lda + lane];
-        Ls[i * PL + lane] = v;
-        Ts[i * PL + lane] = 0.0;
+    // the block's rows are requested in batches of 16 (all in flight at once: each batch is one trip
+    // to memory, and the block is on the factorisation's serial chain), then parked in LDS
+#pragma unroll 1
+    for (int i0 = 0; i0 < NB; i0 += 16) {
+        double v[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int i = i0 + r;
+            v[r] = (i == lane) ? 1.0 : 0.0;
+            if (i < bs && lane <= i) v[r] = A[(int64_t)i * lda + lane];
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            Ls[(i0 + r) * PL + lane] = v[r];
+            Ts[(i0 + r) * PL + lane] = 0.0;
+        }
     }
     wave_lds_sync();
 
