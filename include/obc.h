@@ -25,7 +25,9 @@
  *    Conditions only a kernel can see (a non-positive or non-finite pivot [H^-1]_pp) are
  *    latched on the device and reported by obc_check.
  *  - Results are deterministic: the same inputs give bit-identical outputs.
- *  - Arithmetic is fp32 (obc_invert factorises in fp64 internally and rounds the result).
+ *  - Matrices and results are fp32.  obc_invert, obc_refit and obc_reconstruct_rows factorise in fp64
+ *    internally and round the result; the row solvers keep a row's weights and the diagonal of its
+ *    inverse in fp64 and the matrix itself in fp32.
  */
 #ifndef OBC_H
 #define OBC_H
