@@ -59,7 +59,9 @@ def test_conv256x2304_obq4_sampled_rows(obc, orc):
     q_rtn = (((W - rtn).double() @ Hm) * (W - rtn).double()).sum(dim=1)
     assert torch.all(q_obq < q_rtn)
     # the loss trace sums to that quadratic form (loss identity) on every row
-    assert torch.allclose(res["loss"].double().sum(dim=1), 0.5 * q_obq, rtol=2e-3)
+    dev = float(((res["loss"].double().sum(dim=1) - 0.5 * q_obq).abs() / (0.5 * q_obq)).max())
+    print("loss identity, largest relative deviation over the rows: %.2e" % dev)
+    assert dev < 1e-5
 
 
 def test_ffn768x3072_prune_sampled_row(obc, orc):
@@ -219,7 +221,9 @@ def test_conv256x2304_block4_sampled_rows(obc, orc):
     # loss identity on every row: the block losses add up to 1/2 (w - w^)^T H (w - w^)
     dW = (W - res["W"]).double()
     q = 0.5 * ((dW @ Hd) * dW).sum(dim=1)
-    assert torch.allclose(res["loss"].double().sum(dim=1), q, rtol=2e-3)
+    dev = float(((res["loss"].double().sum(dim=1) - q).abs() / q).max())
+    print("loss identity, largest relative deviation over the rows: %.2e" % dev)
+    assert dev < 1e-5
 
 
 def test_conv256x2304_sequential_obq_with_outlier_heuristic(obc, orc):
