@@ -61,7 +61,7 @@ inline void split_plan(int d, int64_t N, int *S, int64_t *kchunk)
 // Xb is db x N (ldb).  SYM: Ya and Xb are the same matrix and only the tiles on or above the block
 // diagonal are formed.
 template <bool SYM>
-__global__ __launch_bounds__(256) void nt_partial_kernel(const float *__restrict__ Ya, int da,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void nt_partial_kernel(const float *__restrict__ Ya, int da,
                                                          int64_t lda, const float *__restrict__ Xb,
                                                          int db, int64_t ldb, int64_t N,
                                                          int64_t kchunk, float *__restrict__ partial,
@@ -70,22 +70,23 @@ __global__ __launch_bounds__(256) void nt_partial_kernel(const float *__restrict
     __shared__ float As[BK][LDT];
     __shared__ float Bs[BK][LDT];
 
+    const int tile_id = blockIdx.x, slice = blockIdx.y;
     int ti, tj;
     if (SYM) {
-        // upper-triangular tile enumeration: blockIdx.x -> (ti <= tj)
+        // upper-triangular tile enumeration: tile_id -> (ti <= tj)
         const int nt = tiles_of(da);
-        int t = blockIdx.x, rowlen = nt;
+        int t = tile_id, rowlen = nt;
         ti = 0;
         while (t >= rowlen) { t -= rowlen; ++ti; --rowlen; }
         tj = ti + t;
     } else {
         const int ntb = tiles_of(db);
-        ti = blockIdx.x / ntb;
-        tj = blockIdx.x % ntb;
+        ti = tile_id / ntb;
+        tj = tile_id % ntb;
     }
     const bool on_diag = SYM && (ti == tj);
 
-    const int64_t kbeg = (int64_t)blockIdx.y * kchunk;
+    const int64_t kbeg = (int64_t)slice * kchunk;
     const int64_t kend = (kbeg + kchunk < N) ? kbeg + kchunk : N;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -134,20 +135,22 @@ __global__ __launch_bounds__(256) void nt_partial_kernel(const float *__restrict
         }
     };
 
-    if (kbeg < kend) {
-        fetch(Ya, da, lda, ti, kbeg, ra);
-        if (!on_diag) fetch(Xb, db, ldb, tj, kbeg, rb);
-    }
-    for (int64_t k0 = kbeg; k0 < kend; k0 += BK) {
-        stash(As, ra);
-        if (!on_diag) stash(Bs, rb);
-        __syncthreads();
-        if (k0 + BK < kend) {
-            fetch(Ya, da, lda, ti, k0 + BK, ra);
-            if (!on_diag) fetch(Xb, db, ldb, tj, k0 + BK, rb);
+    // A slab that lies wholly inside the slice is fetched without a per-lane condition (rows beyond
+    // the matrix re-read its last row: their products only reach outputs that are never stored), so
+    // that the loop body is straight-line code and the loads overlap with the MFMAs; the slab at the
+    // end of the slice and unaligned inputs take the general loader.
+    auto fetch_full = [&](const float *M, int rows, int64_t ld, int tile, int64_t k0, float4(&r)[2]) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            int f = tid + h * 256;
+            int row = tile * BM + (f >> 2);
+            row = row < rows ? row : rows - 1;
+            r[h] = *reinterpret_cast<const float4 *>(M + (int64_t)row * ld + k0 + (f & 3) * 4);
         }
-        const float(*Bt)[LDT] = on_diag ? As : Bs;
-        const int kl = lane >> 5, il = lane & 31;
+    };
+    const float(*Bt)[LDT] = on_diag ? As : Bs;
+    const int kl = lane >> 5, il = lane & 31;
+    auto mma_slab = [&]() {
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
             float a0 = As[kk + kl][wm * 64 + il];
@@ -159,12 +162,40 @@ __global__ __launch_bounds__(256) void nt_partial_kernel(const float *__restrict
             acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
             acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
         }
+    };
+
+    if (kbeg < kend) {
+        fetch(Ya, da, lda, ti, kbeg, ra);
+        if (!on_diag) fetch(Xb, db, ldb, tj, kbeg, rb);
+    }
+    int64_t k0 = kbeg;
+    if (vec_ok) {
+        // slabs whose successor is a full slab
+        for (; k0 + 2 * BK <= kend; k0 += BK) {
+            stash(As, ra);
+            if (!on_diag) stash(Bs, rb);
+            __syncthreads();
+            fetch_full(Ya, da, lda, ti, k0 + BK, ra);
+            if (!on_diag) fetch_full(Xb, db, ldb, tj, k0 + BK, rb);
+            mma_slab();
+            __syncthreads();
+        }
+    }
+    for (; k0 < kend; k0 += BK) {
+        stash(As, ra);
+        if (!on_diag) stash(Bs, rb);
+        __syncthreads();
+        if (k0 + BK < kend) {
+            fetch(Ya, da, lda, ti, k0 + BK, ra);
+            if (!on_diag) fetch(Xb, db, ldb, tj, k0 + BK, rb);
+        }
+        mma_slab();
         __syncthreads();
     }
 
     // accumulator layout of the 32x32 MFMA: lane holds column (lane % 32) and, for register v,
     // row 8 * (v / 4) + 4 * (lane / 32) + v % 4
-    float *out = partial + (int64_t)blockIdx.y * da * db;
+    float *out = partial + (int64_t)slice * da * db;
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
