@@ -12,9 +12,13 @@
 
 #include "../../include/obc.h"
 
-// One timed kernel launch (only while profiling is on): events on the context's stream.
+// One timed kernel launch (only while profiling is on): events on the context's stream.  Launches
+// that follow each other with nothing in between share an event: the stop of one is the start of
+// the next (an event record costs a few microseconds of stream time; own_start says which scope
+// created `start`).
 struct obc_timed {
     hipEvent_t start, stop;
+    bool own_start;
     int kind;           // OBC_KERNEL_*
     double bytes, flops;   // algorithmic work of the launch
 };
@@ -28,6 +32,8 @@ struct obc_ctx {
     bool profiling;
     std::vector<obc_timed> timed;
     std::vector<hipEvent_t> event_pool;
+    hipEvent_t chain_event;   // stop event of the last timed launch ...
+    bool chain_fresh;         // ... valid as the next one's start: nothing was enqueued after it
 };
 
 // Bracket a launch with events when profiling is on.
@@ -45,15 +51,18 @@ struct obc_scope {
             if (hipEventCreate(&e) != hipSuccess) e = nullptr;
             return e;
         };
-        t.start = get();
+        t.own_start = !ctx->chain_fresh;
+        t.start = t.own_start ? get() : ctx->chain_event;
         t.stop = get();
-        if (!t.start || !t.stop) { on = false; return; }
-        (void)hipEventRecord(t.start, ctx->stream);
+        if (!t.start || !t.stop) { on = false; ctx->chain_fresh = false; return; }
+        if (t.own_start) (void)hipEventRecord(t.start, ctx->stream);
     }
     ~obc_scope()
     {
         if (!on) return;
         (void)hipEventRecord(t.stop, ctx->stream);
+        ctx->chain_event = t.stop;
+        ctx->chain_fresh = true;
         ctx->timed.push_back(t);
     }
 };

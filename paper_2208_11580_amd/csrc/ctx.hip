@@ -17,6 +17,8 @@ int obc_create(obc_ctx **out, void *hip_stream)
     ctx->err[0] = 0;
     ctx->device = 0;
     ctx->profiling = false;
+    ctx->chain_event = nullptr;
+    ctx->chain_fresh = false;
     hipError_t e = hipGetDevice(&ctx->device);
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->d_status, 256);
     if (e == hipSuccess) e = hipMemsetAsync(ctx->d_status, 0, 256, ctx->stream);
@@ -35,7 +37,10 @@ int obc_destroy(obc_ctx *ctx)
     if (!ctx) return OBC_ERR_BAD_ARG;
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->d_status) (void)hipFree(ctx->d_status);
-    for (auto &t : ctx->timed) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
+    for (auto &t : ctx->timed) {
+        if (t.own_start) (void)hipEventDestroy(t.start);
+        (void)hipEventDestroy(t.stop);
+    }
     for (auto e : ctx->event_pool) (void)hipEventDestroy(e);
     delete ctx;
     return OBC_OK;
@@ -44,8 +49,12 @@ int obc_destroy(obc_ctx *ctx)
 int obc_profile_begin(obc_ctx *ctx)
 {
     if (!ctx) return OBC_ERR_BAD_ARG;
-    for (auto &t : ctx->timed) { ctx->event_pool.push_back(t.start); ctx->event_pool.push_back(t.stop); }
+    for (auto &t : ctx->timed) {
+        if (t.own_start) ctx->event_pool.push_back(t.start);
+        ctx->event_pool.push_back(t.stop);
+    }
     ctx->timed.clear();
+    ctx->chain_fresh = false;
     ctx->profiling = true;
     return OBC_OK;
 }
@@ -54,6 +63,7 @@ int obc_profile_end(obc_ctx *ctx, obc_kernel_stat stats[OBC_KERNEL_CLASSES])
 {
     if (!ctx || !stats) return OBC_ERR_BAD_ARG;
     ctx->profiling = false;
+    ctx->chain_fresh = false;
     OBC_HIP(ctx, hipStreamSynchronize(ctx->stream));
     for (int k = 0; k < OBC_KERNEL_CLASSES; ++k) { stats[k].launches = 0; stats[k].ms = stats[k].bytes = stats[k].flops = 0.0; }
     for (auto &t : ctx->timed) {
@@ -64,7 +74,7 @@ int obc_profile_end(obc_ctx *ctx, obc_kernel_stat stats[OBC_KERNEL_CLASSES])
             stats[t.kind].bytes += t.bytes;
             stats[t.kind].flops += t.flops;
         }
-        ctx->event_pool.push_back(t.start);
+        if (t.own_start) ctx->event_pool.push_back(t.start);
         ctx->event_pool.push_back(t.stop);
     }
     ctx->timed.clear();

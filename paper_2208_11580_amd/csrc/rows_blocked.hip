@@ -615,6 +615,7 @@ int blocked_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, in
     if (!ws || ws_bytes < need)
         return obc_fail(ctx, OBC_ERR_WORKSPACE, "row solver: workspace of %zu bytes needed, %zu given", need, ws_bytes);
     hipStream_t st = ctx->stream;
+    ctx->chain_fresh = false;   // the set-up kernels below are not timed: the first timed launch records its own start
 
     InitArgs ia;
     ia.W = W; ia.Hinv = Hinv; ia.live_in = live; ia.stop_counts = stop_counts; ia.d = d;

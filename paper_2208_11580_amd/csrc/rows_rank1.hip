@@ -347,6 +347,7 @@ int rank1_launch(obc_ctx *ctx, int mode, const float *W, const float *Hinv, int 
                  const float *offset, int maxq, const uint8_t *live, int flags, int32_t *order, float *loss,
                  int32_t *codes, float *W_out, float *trace, int out_ld, void *ws, size_t ws_bytes)
 {
+    ctx->chain_fresh = false;   // whatever ran since the last timed launch is not part of this one
     Rank1Args a;
     a.outliers = (flags & OBC_QUANT_OUTLIERS) ? 1 : 0;
     a.blk_c = (mode == MODE_BLOCK) ? blk_c : 0;
