@@ -54,13 +54,18 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_wave_barrier();
 }
 
+// The part of potrf_wave after the block has been parked in LDS: expects the block at lds[i * PL + j]
+// (lower triangle; identity where the block is padded, zeros above the diagonal) and zeros in the
+// NB * PL doubles after it, all visible to the calling wavefront.
+__device__ __forceinline__ void potrf_wave_core(double *__restrict__ A, int lda, int bs, double *__restrict__ Linv,
+                                                int *status, int err, double *lds);
+
 __device__ __forceinline__ void potrf_wave(double *__restrict__ A, int lda, int bs, double *__restrict__ Linv,
                                            int *status, int err, double *lds)
 {
     double *Ls = lds;                         // the block; becomes L (lower triangle)
     double *Ts = lds + NB * PL;               // L^-1
-    double *Xs = lds + 2 * NB * PL;
-    const int lane = threadIdx.x & 63, l16 = lane & 15, lg = lane >> 4;
+    const int lane = threadIdx.x & 63;
     // the block's rows are requested in batches of 16 (all in flight at once: each batch is one trip
     // to memory, and the block is on the factorisation's serial chain), then parked in LDS
 #pragma unroll 1
@@ -80,6 +85,16 @@ __device__ __forceinline__ void potrf_wave(double *__restrict__ A, int lda, int 
     }
     wave_lds_sync();
 
+    potrf_wave_core(A, lda, bs, Linv, status, err, lds);
+}
+
+__device__ __forceinline__ void potrf_wave_core(double *__restrict__ A, int lda, int bs, double *__restrict__ Linv,
+                                                int *status, int err, double *lds)
+{
+    double *Ls = lds;
+    double *Ts = lds + NB * PL;
+    double *Xs = lds + 2 * NB * PL;
+    const int lane = threadIdx.x & 63, l16 = lane & 15, lg = lane >> 4;
     bool bad = false;
 #pragma unroll
     for (int s = 0; s < NB / SB; ++s) {

@@ -6,12 +6,12 @@
 // to fp32 (the fp32 Hessians of correlated post-ReLU activations have condition numbers of
 // 1e4..1e5; an fp32 factorisation would already cost three to four digits of H^-1).
 //
-//   1. A = double(H);  blocked right-looking Cholesky A = L L^T with 64-wide block columns:
-//      the diagonal block is factored and inverted by a single wavefront (16 x 16 sub-blocks in
-//      registers, the rest of the block on the fp64 matrix core out of LDS), the panel below
-//      is a product with the inverted diagonal block, the trailing update is a tiled GEMM.
-//   2. Y = L^-1 by right-looking blocked forward substitution on the identity (two GEMMs per
-//      block row, each over the whole remaining matrix, so all CUs are busy).
+//   1. A = double(H);  blocked right-looking Cholesky A = L L^T with 64-wide block columns, one
+//      launch per block column (chol_step_kernel): every 64 x 64 tile of the trailing update forms
+//      the piece of the panel it needs itself, the workgroup of the next diagonal block goes on to
+//      factor that block and invert its factor on a single wavefront (16 x 16 sub-blocks in
+//      registers, the rest of the block on the fp64 matrix core out of LDS).
+//   2. Y = L^-1 by right-looking blocked forward substitution on the identity, in the same launches.
 //   3. H^-1 = Y^T Y, lower tiles only, mirrored on store so the result is exactly symmetric.
 // All GEMMs run on the fp64 matrix cores (v_mfma_f64_16x16x4_f64), 64x64 tiles staged through LDS.
 #include "dense64.h"
@@ -48,41 +48,196 @@ __global__ __launch_bounds__(256) void gemm64_kernel(GemmArgs g)
     gemm64_tile(g, blockIdx.y, blockIdx.x, lds);
 }
 
-// Two independent products in one launch (blockIdx.z picks the problem): the small products of a
-// factorisation step are latency-bound, so pairing them halves the number of launches.
-__global__ __launch_bounds__(256) void gemm64_dual_kernel(GemmArgs g0, GemmArgs g1)
+// ---- one factorisation step in one launch ----------------------------------------------------
+// 64 x 64 x (K <= 64) products with the whole contraction staged in LDS at once: every operand is
+// requested from memory before any is waited for, so a product costs one trip to memory instead of
+// one per 16-wide slab.  Operand tiles sit k-major in LDS, S[k * PL + i], padded like the
+// factorisation's block (PL = 65) so that both can use the same memory.
+
+// 16 elements per thread of a rows x cols piece of a row-major matrix (element e = tid + 256 h is
+// (e / 64, e % 64): consecutive threads read along a row); zero outside the piece
+__device__ __forceinline__ void tile_fetch(double (&r)[16], const double *__restrict__ p, int64_t ld, int rows, int cols)
 {
-    __shared__ double lds[GEMM_LDS];
-    if (blockIdx.z == 0) gemm64_tile(g0, blockIdx.y, blockIdx.x, lds);
-    else gemm64_tile(g1, blockIdx.y, blockIdx.x, lds);
+#pragma unroll
+    for (int h = 0; h < 16; ++h) {
+        const int e = threadIdx.x + h * 256;
+        const int row = e >> 6, col = e & 63;
+        r[h] = (row < rows && col < cols) ? p[(int64_t)row * ld + col] : 0.0;
+    }
+}
+// park a fetched piece in LDS: element (row, col) at S[row][col], or transposed at S[col][row]
+template <bool TRANSPOSE>
+__device__ __forceinline__ void tile_park(double *S, const double (&r)[16])
+{
+#pragma unroll
+    for (int h = 0; h < 16; ++h) {
+        const int e = threadIdx.x + h * 256;
+        const int row = e >> 6, col = e & 63;
+        S[TRANSPOSE ? col * PL + row : row * PL + col] = r[h];
+    }
+}
+// acc(i, j) = sum_k As[k][i] Bs[k][j] over all 64 k; wave (wm, wn) of the 2 x 2 owns 32 x 32 outputs.
+// v_mfma_f64_16x16x4: lane l supplies a(i = l % 16, k = l / 16) and b(k = l / 16, j = l % 16) and
+// holds c(4 r + l / 16, l % 16) in accumulator register r.
+__device__ __forceinline__ void tile_mma(doublex4 (&acc)[2][2], const double *As, const double *Bs)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1, kl = lane >> 4, il = lane & 15;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) acc[a][b] = doublex4{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int kk = 0; kk < NB; kk += 4) {
+        const double a0 = As[(kk + kl) * PL + wm * 32 + il], a1 = As[(kk + kl) * PL + wm * 32 + 16 + il];
+        const double b0 = Bs[(kk + kl) * PL + wn * 32 + il], b1 = Bs[(kk + kl) * PL + wn * 32 + 16 + il];
+        acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
+        acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
+        acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
+        acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
+    }
+}
+// visit the calling thread's 16 accumulator entries: f(row, col, value)
+template <typename F>
+__device__ __forceinline__ void tile_each(doublex4 (&acc)[2][2], F f)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                f(wm * 32 + a * 16 + 4 * r + (lane >> 4), wn * 32 + b * 16 + (lane & 15), (double)acc[a][b][r]);
+}
+// set them: acc(row, col) = f(row, col)
+template <typename F>
+__device__ __forceinline__ void tile_fill(doublex4 (&acc)[2][2], F f)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                acc[a][b][r] = f(wm * 32 + a * 16 + 4 * r + (lane >> 4), wn * 32 + b * 16 + (lane & 15));
 }
 
-// The trailing update of a factorisation step (g0: A22 -= L21 L21^T, lower tiles) and the update of
-// Y below the step's block row (g1), with the NEXT step's diagonal block looked ahead: the workgroup
-// that updates tile (0, 0) of A22 -- the next diagonal block -- goes on to factor it and invert its
-// factor (one wavefront), while the other workgroups do the rest of the two updates.  The
-// factorisation of a diagonal block (about 35 us on one wavefront) is the longest item of a step; this
-// takes it off the stream's serial chain.  That workgroup is the first one dispatched.
-struct LookAhead {
-    double *Akk;     // tile (0, 0) of A22
-    int lda, bs;
-    double *Linv;    // NB x NB out
+template <typename F>
+__device__ __forceinline__ void tile_each2(doublex4 (&x)[2][2], doublex4 (&y)[2][2], F f)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                f(wm * 32 + a * 16 + 4 * r + (lane >> 4), wn * 32 + b * 16 + (lane & 15), (double)x[a][b][r], (double)y[a][b][r]);
+}
+
+// One step of the factorisation (block column kb, columns k0 .. k0 + bs) in ONE launch.  With
+// T = L_kk^-1 and G = T^T T = A_kk^-1 (both left by the step before), P = the block column below the
+// diagonal block as the earlier trailing updates left it (L21 = P T^T is never formed or stored),
+// and Yk = block row kb of Y before its own solve:
+//   z = 0, tile (i, j), j <= i:   A22[i, j] -= (P_i G) P_j^T            (= L21_i L21_j^T)
+//   z = 1, tile (i, c):           Y[below][i, c] -= (P_i G) Yk[c]       (= L21_i (T Yk)[c])
+//   z = 2, tile c:                Y[kb - 1][c] = T_prev Y[kb - 1][c]    (the previous block row's solve:
+//                                 nobody reads its unsolved values any more)
+// Every z = 0 / 1 workgroup forms its own Q = P_i G in LDS first: the panel solve that used to be a
+// launch of its own on the stream's serial chain now costs each tile one more small product.  The
+// workgroup of tile (0, 0), the first one dispatched, keeps the block it has just updated -- the next
+// diagonal block -- in LDS, factors it there on one wavefront, and leaves T and G for the next step.
+// Per step the stream waits for: one trip to memory, two tile products, one 64 x 64 factorisation,
+// one product out of LDS.
+struct StepArgs {
+    double *A, *Y;
+    int d, k0, bs;
+    const double *T, *G;         // of this step's diagonal block (NB x NB, row-major)
+    const double *Tprev;         // of the previous step's; its block row starts at kprev0 (bsprev rows,
+    int kprev0, bsprev;          // ncprev = kprev0 + bsprev columns); bsprev = 0: nothing to finish
+    double *Tnext, *Gnext;       // out: of the next diagonal block
     int *status;
 };
 
-__global__ __launch_bounds__(256) void trailing_lookahead_kernel(GemmArgs g0, GemmArgs g1, LookAhead la)
+__global__ __launch_bounds__(256) void chol_step_kernel(StepArgs s)
 {
-    // (the factorisation reuses the tile product's LDS: the two never overlap in time)
-    __shared__ double lds[POTRF_LDS > GEMM_LDS ? POTRF_LDS : GEMM_LDS];
-    if (blockIdx.z != 0) {
-        gemm64_tile(g1, blockIdx.y, blockIdx.x, lds);
+    // (the factorisation reuses the products' LDS: they never overlap in time)
+    __shared__ double lds[POTRF_LDS];
+    double *As = lds, *Bs = lds + NB * PL;
+    const int d = s.d, k0 = s.k0, bs = s.bs;
+    const int nc = k0 + bs, m = d - nc;
+    doublex4 acc[2][2];
+    if (blockIdx.z == 2) {
+        const int ncprev = s.kprev0 + s.bsprev, c0 = blockIdx.x * NB;
+        if (blockIdx.y != 0 || s.bsprev <= 0 || c0 >= ncprev) return;
+        double *Yp = s.Y + (int64_t)s.kprev0 * d + c0;
+        const int Nc = (ncprev - c0 < NB) ? ncprev - c0 : NB;
+        double ra[16], rb[16];
+        tile_fetch(ra, s.Tprev, NB, s.bsprev, s.bsprev);     // a(i, k) = T[i][k]
+        tile_fetch(rb, Yp, d, s.bsprev, Nc);                 // b(k, j) = Y[k][j]
+        tile_park<true>(As, ra);
+        tile_park<false>(Bs, rb);
+        __syncthreads();
+        tile_mma(acc, As, Bs);
+        // the workgroup overwrites exactly the block it has read
+        tile_each(acc, [&](int i, int j, double v) { if (i < s.bsprev && j < Nc) Yp[(int64_t)i * d + j] = v; });
         return;
     }
-    gemm64_tile(g0, blockIdx.y, blockIdx.x, lds);
-    if (blockIdx.x != 0 || blockIdx.y != 0) return;
-    __threadfence();                           // the tile's entries, written by four waves, ...
-    __syncthreads();                           // ... are read back by the first
-    if (threadIdx.x < 64) potrf_wave(la.Akk, la.lda, la.bs, la.Linv, la.status, OBC_ERR_NOT_SPD, lds);
+    const int ti = blockIdx.y, tj = blockIdx.x;
+    const int i0 = ti * NB;
+    if (i0 >= m) return;
+    if (blockIdx.z == 0 && tj > ti) return;
+    if (blockIdx.z == 1 && tj * NB >= nc) return;
+    const int Mi = (m - i0 < NB) ? m - i0 : NB;
+    // the second product's right operand and the tile it updates
+    const bool upd_a = (blockIdx.z == 0);
+    const int j0 = tj * NB;
+    const int Nj = upd_a ? ((m - j0 < NB) ? m - j0 : NB) : ((nc - j0 < NB) ? nc - j0 : NB);
+    double *C = upd_a ? s.A + (int64_t)(nc + i0) * d + nc + j0 : s.Y + (int64_t)(nc + i0) * d + j0;
+    {
+        double rp[16], rg[16];
+        tile_fetch(rp, s.A + (int64_t)(nc + i0) * d + k0, d, Mi, bs);    // a(i, k) = P_i[i][k]
+        tile_fetch(rg, s.G, NB, bs, bs);                                   // b(k, j) = G[k][j]
+        tile_park<true>(As, rp);
+        tile_park<false>(Bs, rg);
+    }
+    double rb[16];
+    if (upd_a) tile_fetch(rb, s.A + (int64_t)(nc + j0) * d + k0, d, Nj, bs);   // b(k, j) = P_j[j][k]
+    else tile_fetch(rb, s.Y + (int64_t)k0 * d + j0, d, bs, Nj);                 // b(k, j) = Yk[k][j]
+    doublex4 cold[2][2];
+    tile_fill(cold, [&](int i, int j) { return (i < Mi && j < Nj) ? C[(int64_t)i * d + j] : 0.0; });
+    __syncthreads();
+    tile_mma(acc, As, Bs);                      // Q = P_i G
+    __syncthreads();                            // everybody is done reading As / Bs
+    tile_each(acc, [&](int i, int j, double v) { As[j * PL + i] = v; });   // a(i, k) = Q[i][k]
+    if (upd_a) tile_park<true>(Bs, rb);
+    else tile_park<false>(Bs, rb);
+    __syncthreads();
+    tile_mma(acc, As, Bs);                      // Q B
+    const bool chain = upd_a && ti == 0 && tj == 0;
+    if (!chain) {
+        tile_each2(acc, cold, [&](int i, int j, double v, double c) {
+            if (i < Mi && j < Nj) C[(int64_t)i * d + j] = c - v;
+        });
+        return;
+    }
+    // the next diagonal block goes straight into the factorisation's LDS layout (lower triangle,
+    // identity where the block is padded), the inverse's area is cleared
+    __syncthreads();                            // everybody is done reading As / Bs
+    tile_each2(acc, cold, [&](int i, int j, double v, double c) {
+        As[i * PL + j] = (i < Mi && j <= i) ? c - v : (i == j ? 1.0 : 0.0);
+        Bs[i * PL + j] = 0.0;
+    });
+    __syncthreads();
+    if (threadIdx.x < 64) potrf_wave_core(C, d, Mi, s.Tnext, s.status, OBC_ERR_NOT_SPD, lds);
+    __syncthreads();                            // T of the next block, in LDS where the core left it
+    tile_mma(acc, Bs, Bs);                      // G = T^T T
+    tile_each(acc, [&](int i, int j, double v) { s.Gnext[i * NB + j] = v; });
 }
 
 // Y = identity (d x d)
@@ -103,7 +258,7 @@ int obc_invert_workspace_bytes(int d, size_t *bytes)
     if (!bytes || d <= 0) return OBC_ERR_BAD_ARG;
     size_t nblk = (size_t)(d + NB - 1) / NB;
     size_t mat = obc_align_up((size_t)d * d * sizeof(double), 256);
-    size_t blocks = obc_align_up(nblk * NB * NB * sizeof(double), 256);
+    size_t blocks = obc_align_up(2 * nblk * NB * NB * sizeof(double), 256);   // T and G of every diagonal block
     *bytes = 2 * mat + blocks;
     return OBC_OK;
 }
@@ -129,44 +284,47 @@ int factor_inverse(obc_ctx *ctx, const float *H, int d, void *ws, double **Yout)
     eye_f64_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(Y, d);
     OBC_LAUNCH_CHECK(ctx, "f32_to_f64_kernel");
 
-    auto dual_grid = [](const GemmArgs &a, const GemmArgs &b) {
-        unsigned gx = (unsigned)((((a.N > b.N) ? a.N : b.N) + NB - 1) / NB);
-        unsigned gy = (unsigned)((((a.M > b.M) ? a.M : b.M) + NB - 1) / NB);
-        return dim3(gx, gy, 2);
-    };
-
-    // 1 + 2. Cholesky A = L L^T and Y = L^-1 together, block column by block column.  Step kb:
-    //   (L_kk and its inverse: by the previous step's launch B; the first block by a launch of its own)
-    //   launch A: L21 = A21 Linv_kk^T   |  Y[kb] = Linv_kk Y[kb]
-    //   launch B: A22 -= L21 L21^T (lower tiles)  |  Y[rows below] -= L21 Y[kb]
-    //             | the next diagonal block, once updated, is factored and its factor inverted
-    // (Y starts as the identity: forward substitution on the identity, right-looking; before step
-    // kb its block row kb holds I_kb - sum_{j<kb} L[kb,j] Y[j], non-zero only in columns < k0 + bs.)
+    // 1 + 2. Cholesky A = L L^T and Y = L^-1 together, block column by block column, one launch per
+    // step (chol_step_kernel); the first diagonal block and the last block row have launches of
+    // their own.  (Y starts as the identity: forward substitution on the identity, right-looking;
+    // before step kb its block row kb holds I_kb - sum_{j<kb} L[kb,j] Y[j], non-zero only in columns
+    // < k0 + bs.)
+    double *Gb = Lb + (int64_t)nblk * NB * NB;
+    {
+        const int bs0 = d < NB ? d : NB;
+        potrf_wave_kernel<<<1, 64, 0, st>>>(A, d, bs0, Lb, ctx->d_status, 0, 0, OBC_ERR_NOT_SPD);
+        gemm64_kernel<<<1, 256, 0, st>>>(mk(NB, NB, NB, 1.0, Lb, 1, NB, Lb, NB, 1, 0.0, Gb, NB, 0, 0, nullptr));
+    }
+    int kprev0 = 0, bsprev = 0;
     for (int kb = 0; kb < nblk; ++kb) {
         const int k0 = kb * NB;
         const int bs = (d - k0 < NB) ? d - k0 : NB;
         const int nc = k0 + bs;
-        const int m = d - k0 - bs;
-        double *Akk = A + (int64_t)k0 * d + k0;
-        double *Lk = Lb + (int64_t)kb * NB * NB;
-        double *Yk = Y + (int64_t)k0 * d;
-        if (kb == 0) potrf_wave_kernel<<<1, 64, 0, st>>>(Akk, d, bs, Lk, ctx->d_status, 0, 0, OBC_ERR_NOT_SPD);
-        // each workgroup overwrites exactly the rows / columns it has read
-        GemmArgs trsm_row = mk(bs, nc, bs, 1.0, Lk, NB, 1, Yk, d, 1, 0.0, Yk, d, 0, 0, nullptr);
+        const int m = d - nc;
+        double *Tk = Lb + (int64_t)kb * NB * NB;
         if (m > 0) {
-            double *A21 = A + (int64_t)(k0 + bs) * d + k0;
-            double *A22 = A + (int64_t)(k0 + bs) * d + (k0 + bs);
-            GemmArgs panel = mk(m, bs, bs, 1.0, A21, d, 1, Lk, 1, NB, 0.0, A21, d, 0, 0, nullptr);
-            gemm64_dual_kernel<<<dual_grid(panel, trsm_row), 256, 0, st>>>(panel, trsm_row);
-            GemmArgs trail = mk(m, m, bs, -1.0, A21, d, 1, A21, 1, d, 1.0, A22, d, 1, 0, nullptr);
-            GemmArgs trsm_upd = mk(m, nc, bs, -1.0, A21, d, 1, Yk, d, 1, 1.0, Y + (int64_t)(k0 + bs) * d, d, 0, 0, nullptr);
-            LookAhead la;
-            la.Akk = A22; la.lda = d; la.bs = (m < NB) ? m : NB; la.Linv = Lk + (int64_t)NB * NB;
-            la.status = ctx->d_status;
-            trailing_lookahead_kernel<<<dual_grid(trail, trsm_upd), 256, 0, st>>>(trail, trsm_upd, la);
+            StepArgs sa;
+            sa.A = A; sa.Y = Y; sa.d = d; sa.k0 = k0; sa.bs = bs;
+            sa.T = Tk; sa.G = Gb + (int64_t)kb * NB * NB;
+            sa.Tprev = (kb > 0) ? Tk - (int64_t)NB * NB : nullptr;
+            sa.kprev0 = kprev0; sa.bsprev = bsprev;
+            sa.Tnext = Tk + (int64_t)NB * NB; sa.Gnext = Gb + (int64_t)(kb + 1) * NB * NB;
+            sa.status = ctx->d_status;
+            const int tm = (m + NB - 1) / NB, tc = (nc + NB - 1) / NB;
+            chol_step_kernel<<<dim3((unsigned)(tm > tc ? tm : tc), (unsigned)tm, 3), 256, 0, st>>>(sa);
         } else {
-            gemm64_kernel<<<grid64(bs, nc), 256, 0, st>>>(trsm_row);
+            // the last block column: finish the previous block row and this one
+            if (bsprev > 0) {
+                double *Yp = Y + (int64_t)kprev0 * d;
+                const int ncp = kprev0 + bsprev;
+                gemm64_kernel<<<grid64(bsprev, ncp), 256, 0, st>>>(
+                    mk(bsprev, ncp, bsprev, 1.0, Tk - (int64_t)NB * NB, NB, 1, Yp, d, 1, 0.0, Yp, d, 0, 0, nullptr));
+            }
+            double *Yk = Y + (int64_t)k0 * d;
+            gemm64_kernel<<<grid64(bs, nc), 256, 0, st>>>(mk(bs, nc, bs, 1.0, Tk, NB, 1, Yk, d, 1, 0.0, Yk, d, 0, 0, nullptr));
         }
+        kprev0 = k0;
+        bsprev = bs;
     }
     OBC_LAUNCH_CHECK(ctx, "factorisation kernels");
     *Yout = Y;
