@@ -212,10 +212,21 @@ __device__ __forceinline__ void potrf_wave_core(double *__restrict__ A, int lda,
             for (int r = 0; r < 4; ++r) Ts[(SB * ib + 4 * r + lg) * PL + SB * s + l16] = y[r];
             wave_lds_sync();
         }
-#pragma unroll 4
-    for (int i = 0; i < NB; ++i) {
-        if (i < bs && lane <= i) A[(int64_t)i * lda + lane] = Ls[i * PL + lane];
-        Linv[i * NB + lane] = (lane <= i) ? Ts[i * PL + lane] : 0.0;
+    // results to memory, 16 rows per batch (all LDS reads of a batch in flight at once)
+#pragma unroll 1
+    for (int i0 = 0; i0 < NB; i0 += 16) {
+        double lv[16], tv[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            lv[r] = Ls[(i0 + r) * PL + lane];
+            tv[r] = Ts[(i0 + r) * PL + lane];
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int i = i0 + r;
+            if (i < bs && lane <= i) A[(int64_t)i * lda + lane] = lv[r];
+            Linv[i * NB + lane] = (lane <= i) ? tv[r] : 0.0;
+        }
     }
     if (lane == 0 && bad) obc_latch(status, err);
 }

@@ -140,6 +140,200 @@ __device__ __forceinline__ void tile_each2(doublex4 (&x)[2][2], doublex4 (&y)[2]
                 f(wm * 32 + a * 16 + 4 * r + (lane >> 4), wn * 32 + b * 16 + (lane & 15), (double)x[a][b][r], (double)y[a][b][r]);
 }
 
+// The diagonal-block factorisation of potrf_wave for a whole workgroup of four wavefronts, block
+// already in LDS (layout and contract of potrf_wave_core; the factor is not written out).  The 64
+// dependent column steps stay on wavefront 0, everything else moves off its chain:
+//  * wavefront 0 factors a whole 16-column panel at a time -- lane l holds row (16 s + l) of the
+//    panel, so the sub-blocks below the diagonal one come out of the same instructions as the
+//    diagonal sub-block (no product with its inverse);
+//  * the inverse of diagonal sub-block s - 1 is computed by wavefront 1 while wavefront 0 factors
+//    panel s;
+//  * the trailing sub-block updates of a panel are dealt to all four wavefronts, the three block
+//    columns of the off-diagonal part of L^-1 to three of them, the final stores to all.
+// LDS: POTRF_LDS doubles as for potrf_wave, then two more 16 x 17 scratch sub-blocks, then 2 x 16
+// reciprocal pivots.
+// rsqrt_f64 (hardware estimate and two Newton steps) one operation at a time, so that the caller can
+// place the nine dependent operations among independent work: stage 0 .. 8, result in r after stage 8
+__device__ __forceinline__ void rsqrt_stage(int st, double x, double &r, double &a)
+{
+    switch (st) {
+    case 0: r = __builtin_amdgcn_rsq(x); break;
+    case 1: case 5: a = r * r; break;
+    case 2: case 6: a = x * a; break;
+    case 3: case 7: a = fma(-0.5, a, 1.5); break;
+    case 4: case 8: r = r * a; break;
+    default: break;
+    }
+}
+
+constexpr int POTRF_WG_LDS = POTRF_LDS + 2 * SB * (SB + 1) + 2 * SB;
+
+__device__ __forceinline__ void potrf_wg_core(double *__restrict__ Linv, int *status, int err, double *lds)
+{
+    double *Ls = lds;
+    double *Ts = lds + NB * PL;
+    double *Xs0 = lds + 2 * NB * PL;
+    double *Rj = lds + POTRF_LDS + 2 * SB * (SB + 1);
+    const int lane = threadIdx.x & 63, l16 = lane & 15, lg = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    bool bad = false;
+
+    // inverse of the 16 x 16 factor at sub-block o (rows in LDS, reciprocal pivots in rjs), lane c
+    // computes column c:  t[i] = (delta_ic - sum_{k<i} L[i][k] t[k]) / L[i][i]
+    auto invert_diag = [&](int o, const double *rjs) {
+        double row[SB], t[SB];
+#pragma unroll
+        for (int c = 0; c < SB; ++c) row[c] = Ls[(o + l16) * PL + o + c];
+#pragma unroll
+        for (int i = 0; i < SB; ++i) {
+            double acc = (l16 == i) ? 1.0 : 0.0;
+            // the lane to read from, made to depend on the previous row's result: otherwise
+            // the lane reads of all rows are issued up front and overflow the scalar registers
+            int sel = i;
+            if (i > 0) asm volatile("" : "+s"(sel) : "v"(t[i > 0 ? i - 1 : 0]));
+#pragma unroll
+            for (int k = 0; k < i; ++k) acc = fma(-readlane_f64(row[k], sel), t[k], acc);
+            t[i] = acc * rjs[i];
+        }
+        if (lane < SB) {
+#pragma unroll
+            for (int c = 0; c < SB; ++c) Ts[(o + c) * PL + o + lane] = t[c];
+        }
+    };
+
+#pragma unroll
+    for (int s = 0; s < NB / SB; ++s) {
+        const int o = SB * s;
+        if (wave == 0) {
+            // ---- panel s: row (o + lane) in registers
+            int ls = lane;
+            asm volatile("" : "+v"(ls));   // (an opaque copy per panel: keeps the lane masks out of scalar registers)
+            const bool has = o + lane < NB;
+            double row[SB], rj[SB];
+#pragma unroll
+            for (int c = 0; c < SB; ++c) row[c] = has ? Ls[(o + lane) * PL + o + c] : 0.0;
+            // The pivot of column j + 1 is known as soon as column j has updated row entry j + 1: its
+            // reciprocal square root (a chain of dependent fp64 operations) is started right there,
+            // among the remaining updates of column j, instead of after them.
+            double pj = readlane_f64(row[0], 0);
+            if (!(pj > 0.0) || !(pj < __builtin_inf())) { bad = true; pj = 1.0; }
+            double r = rsqrt_f64(pj);
+#pragma unroll
+            for (int j = 0; j < SB; ++j) {
+                rj[j] = r;                                          // 1 / L[j][j]
+                const double cj = row[j] * r;
+                row[j] = (ls == j) ? pj * r : (ls > j ? cj : 0.0);
+                const double mine = (ls > j) ? cj : 0.0;            // L[o + lane][j] below the diagonal
+                double pn = 1.0, rn = 1.0, an = 0.0;
+#pragma unroll
+                for (int c = j + 1; c < SB; ++c) {
+                    const double lcj = readlane_f64(cj, c);         // L[o + c][j]
+                    row[c] = fma(-mine, lcj, row[c]);
+                    // pin the update here: left to itself the compiler defers it to the column's
+                    // turn and keeps every L[c][j] alive in scalar registers until then
+                    asm volatile("" : "+v"(row[c]));
+                    if (c == j + 1) {
+                        pn = readlane_f64(row[c], c);
+                        if (!(pn > 0.0) || !(pn < __builtin_inf())) { bad = true; pn = 1.0; }
+                    }
+                    rsqrt_stage(c - (j + 1), pn, rn, an);           // one operation of it per update
+                }
+#pragma unroll
+                for (int st = (SB - 1 - j > 0 ? SB - 1 - j : 0); st < 9; ++st) rsqrt_stage(st, pn, rn, an);
+                pj = pn;
+                r = rn;
+            }
+            if (has) {
+#pragma unroll
+                for (int c = 0; c < SB; ++c) Ls[(o + lane) * PL + o + c] = row[c];
+            }
+            if (lane == 0) {
+#pragma unroll
+                for (int j = 0; j < SB; ++j) Rj[(s & 1) * SB + j] = rj[j];
+            }
+        } else if (wave == 1 && s > 0) {
+            double rjs[SB];
+#pragma unroll
+            for (int i = 0; i < SB; ++i) rjs[i] = Rj[((s - 1) & 1) * SB + i];
+            invert_diag(o - SB, rjs);
+        }
+        __syncthreads();                       // panel s (and the inverse of sub-block s - 1) in LDS
+        // ---- trailing sub-blocks: A_ij -= L_is L_js^T  (s < j <= i), dealt to the four wavefronts
+        int pair = 0;
+#pragma unroll
+        for (int ib = s + 1; ib < NB / SB; ++ib)
+#pragma unroll
+            for (int jb = s + 1; jb <= ib; ++jb, ++pair) {
+                if ((pair & 3) != wave) continue;
+                doublex4 acc;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[r] = Ls[(SB * ib + 4 * r + lg) * PL + SB * jb + l16];
+#pragma unroll
+                for (int kc = 0; kc < SB / 4; ++kc) {
+                    const double av = -Ls[(SB * ib + l16) * PL + o + 4 * kc + lg];
+                    const double bv = Ls[(SB * jb + l16) * PL + o + 4 * kc + lg];
+                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) Ls[(SB * ib + 4 * r + lg) * PL + SB * jb + l16] = acc[r];
+            }
+        if (s + 1 < NB / SB) __syncthreads();
+    }
+    if (wave == 1) {
+        double rjs[SB];
+#pragma unroll
+        for (int i = 0; i < SB; ++i) rjs[i] = Rj[((NB / SB - 1) & 1) * SB + i];
+        invert_diag(NB - SB, rjs);
+    }
+    __syncthreads();
+    // ---- off-diagonal sub-blocks of T = L^-1: block column s on wavefront s, top to bottom
+    //      T_is = -T_ii sum_{s <= k < i} L_ik T_ks  (a wavefront only reads what it wrote itself,
+    //      the factor and the diagonal sub-blocks)
+#pragma unroll
+    for (int s = 0; s + 1 < NB / SB; ++s) {
+        if (wave != s) continue;
+        double *Xs = Xs0 + s * SB * (SB + 1);
+#pragma unroll
+        for (int ib = s + 1; ib < NB / SB; ++ib) {
+            doublex4 x = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int kb = s; kb < ib; ++kb)
+#pragma unroll
+                for (int kc = 0; kc < SB / 4; ++kc) {
+                    const double av = Ls[(SB * ib + l16) * PL + SB * kb + 4 * kc + lg];
+                    const double bv = Ts[(SB * kb + 4 * kc + lg) * PL + SB * s + l16];
+                    x = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, x, 0, 0, 0);
+                }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) Xs[(4 * r + lg) * (SB + 1) + l16] = x[r];
+            wave_lds_sync();
+            doublex4 y = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int kc = 0; kc < SB / 4; ++kc) {
+                const double av = -Ts[(SB * ib + l16) * PL + SB * ib + 4 * kc + lg];
+                const double bv = Xs[(4 * kc + lg) * (SB + 1) + l16];
+                y = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, y, 0, 0, 0);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) Ts[(SB * ib + 4 * r + lg) * PL + SB * s + l16] = y[r];
+            wave_lds_sync();
+        }
+    }
+    __syncthreads();
+    // ---- L^-1 to memory (it also stays in LDS for the caller): 16 rows per wavefront
+    {
+        double tv[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) tv[r] = Ts[(wave * 16 + r) * PL + lane];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int i = wave * 16 + r;
+            Linv[i * NB + lane] = (lane <= i) ? tv[r] : 0.0;
+        }
+    }
+    if (threadIdx.x == 0 && bad) obc_latch(status, err);
+}
+
 // One step of the factorisation (block column kb, columns k0 .. k0 + bs) in ONE launch.  With
 // T = L_kk^-1 and G = T^T T = A_kk^-1 (both left by the step before), P = the block column below the
 // diagonal block as the earlier trailing updates left it (L21 = P T^T is never formed or stored),
@@ -167,7 +361,7 @@ struct StepArgs {
 __global__ __launch_bounds__(256) void chol_step_kernel(StepArgs s)
 {
     // (the factorisation reuses the products' LDS: they never overlap in time)
-    __shared__ double lds[POTRF_LDS];
+    __shared__ double lds[POTRF_WG_LDS];
     double *As = lds, *Bs = lds + NB * PL;
     const int d = s.d, k0 = s.k0, bs = s.bs;
     const int nc = k0 + bs, m = d - nc;
@@ -234,8 +428,9 @@ __global__ __launch_bounds__(256) void chol_step_kernel(StepArgs s)
         Bs[i * PL + j] = 0.0;
     });
     __syncthreads();
-    if (threadIdx.x < 64) potrf_wave_core(C, d, Mi, s.Tnext, s.status, OBC_ERR_NOT_SPD, lds);
-    __syncthreads();                            // T of the next block, in LDS where the core left it
+    // (the factor itself is not needed again: T and G carry the step)
+    potrf_wg_core(s.Tnext, s.status, OBC_ERR_NOT_SPD, lds);
+    __syncthreads();                            // T of the next block, in LDS where the factorisation left it
     tile_mma(acc, Bs, Bs);                      // G = T^T T
     tile_each(acc, [&](int i, int j, double v) { s.Gnext[i * NB + j] = v; });
 }
