@@ -76,17 +76,20 @@ __device__ __forceinline__ void tile_park(double *S, const double (&r)[16])
         S[TRANSPOSE ? col * PL + row : row * PL + col] = r[h];
     }
 }
-// acc(i, j) = sum_k As[k][i] Bs[k][j] over all 64 k; wave (wm, wn) of the 2 x 2 owns 32 x 32 outputs.
+// acc(i, j) (+)= sum_k As[k][i] Bs[k][j] over all 64 k; wave (wm, wn) of the 2 x 2 owns 32 x 32 outputs.
 // v_mfma_f64_16x16x4: lane l supplies a(i = l % 16, k = l / 16) and b(k = l / 16, j = l % 16) and
 // holds c(4 r + l / 16, l % 16) in accumulator register r.
+template <bool ACCUMULATE = false>
 __device__ __forceinline__ void tile_mma(doublex4 (&acc)[2][2], const double *As, const double *Bs)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1, kl = lane >> 4, il = lane & 15;
+    if (!ACCUMULATE) {
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) acc[a][b] = doublex4{0.0, 0.0, 0.0, 0.0};
+            for (int b = 0; b < 2; ++b) acc[a][b] = doublex4{0.0, 0.0, 0.0, 0.0};
+    }
 #pragma unroll
     for (int kk = 0; kk < NB; kk += 4) {
         const double a0 = As[(kk + kl) * PL + wm * 32 + il], a1 = As[(kk + kl) * PL + wm * 32 + 16 + il];
@@ -138,6 +141,55 @@ __device__ __forceinline__ void tile_each2(doublex4 (&x)[2][2], doublex4 (&y)[2]
 #pragma unroll
             for (int r = 0; r < 4; ++r)
                 f(wm * 32 + a * 16 + 4 * r + (lane >> 4), wn * 32 + b * 16 + (lane & 15), (double)x[a][b][r], (double)y[a][b][r]);
+}
+
+// Step 3: tile (ti, tj), tj <= ti, of H^-1 = Y^T Y with Y = L^-1 lower triangular: the sum runs over
+// k >= the tile's first row only.  Y's rows are the contraction index, so both operand tiles are
+// pieces of Y as they lie in memory; 64-deep slabs, requested two ahead.  The result is rounded to fp32 and written on both sides of the diagonal.
+__global__ __launch_bounds__(256) void yty_kernel(const double *__restrict__ Y, int d, float *__restrict__ H)
+{
+    __shared__ double lds[2 * NB * PL];
+    double *As = lds, *Bs = lds + NB * PL;
+    const int ti = blockIdx.y, tj = blockIdx.x;
+    if (tj > ti) return;
+    const int i0 = ti * NB, j0 = tj * NB;
+    const int Mi = (d - i0 < NB) ? d - i0 : NB, Nj = (d - j0 < NB) ? d - j0 : NB;
+    const bool diag = (ti == tj);
+    doublex4 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) acc[a][b] = doublex4{0.0, 0.0, 0.0, 0.0};
+    // two slabs are in flight at any time (the long tiles near the top of the triangle are a chain of
+    // d / 64 slabs each: what they wait for is memory latency)
+    double ra[2][16], rb[2][16];
+    auto fetch = [&](int k0, double (&fa)[16], double (&fb)[16]) {
+        const int kr = (d - k0 < NB) ? d - k0 : NB;
+        tile_fetch(fa, Y + (int64_t)k0 * d + i0, d, kr, Mi);              // a(i, k) = Y[k][i0 + i]
+        if (!diag) tile_fetch(fb, Y + (int64_t)k0 * d + j0, d, kr, Nj);   // b(k, j) = Y[k][j0 + j]
+    };
+    auto slab = [&](int knext, double (&fa)[16], double (&fb)[16]) {
+        tile_park<false>(As, fa);
+        if (!diag) tile_park<false>(Bs, fb);
+        __syncthreads();
+        if (knext < d) fetch(knext, fa, fb);
+        tile_mma<true>(acc, As, diag ? As : Bs);
+        __syncthreads();
+    };
+    fetch(i0, ra[0], rb[0]);
+    if (i0 + NB < d) fetch(i0 + NB, ra[1], rb[1]);
+    for (int k0 = i0; k0 < d; k0 += 2 * NB) {
+        slab(k0 + 2 * NB, ra[0], rb[0]);
+        if (k0 + NB >= d) break;
+        slab(k0 + 3 * NB, ra[1], rb[1]);
+    }
+    tile_each(acc, [&](int i, int j, double v) {
+        if (i < Mi && j < Nj) {
+            const float f = (float)v;
+            H[(int64_t)(i0 + i) * d + j0 + j] = f;
+            if (!diag) H[(int64_t)(j0 + j) * d + i0 + i] = f;
+        }
+    });
 }
 
 // The diagonal-block factorisation of potrf_wave for a whole workgroup of four wavefronts, block
@@ -529,8 +581,8 @@ int factor_inverse(obc_ctx *ctx, const float *H, int d, void *ws, double **Yout)
 // 3. H^-1 = Y^T Y, rounded to fp32, mirrored
 int inverse_from_factor(obc_ctx *ctx, const double *Y, int d, float *H)
 {
-    gemm64_kernel<<<grid64(d, d), 256, 0, ctx->stream>>>(mk(d, d, d, 1.0, Y, 1, d, Y, d, 1, 0.0, nullptr, d, 1, 2, H));
-    OBC_LAUNCH_CHECK(ctx, "gemm64_kernel");
+    yty_kernel<<<grid64(d, d), 256, 0, ctx->stream>>>(Y, d, H);
+    OBC_LAUNCH_CHECK(ctx, "yty_kernel");
     return OBC_OK;
 }
 
