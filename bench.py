@@ -305,7 +305,10 @@ def membench(ctx):
                                          ("copy_streaming", 2, True, 2 * nbytes)):
         ms = ctx.obc_membench(kind, src, dst, nbytes, reps=5, streaming=streaming)
         res[name] = {"ms": ms, "GB/s": moved / (1e-3 * ms) / 1e9, "frac_of_peak": moved / (1e-3 * ms) / 1e9 / HBM_PEAK_GBS}
-    print(json.dumps({"membench": res, "peak_GB/s": HBM_PEAK_GBS}))
+    # the matrix cores on a loop of independent MFMA instructions (data-sheet: 157.3 / 78.6 TFLOP/s)
+    mfma = {"f32_32x32x2_TFLOP/s": ctx.obc_mfmabench(0), "f64_16x16x4_TFLOP/s": ctx.obc_mfmabench(1),
+            "f32_peak": MFMA_F32_PEAK_TFLOPS, "f64_peak": 78.6}
+    print(json.dumps({"membench": res, "peak_GB/s": HBM_PEAK_GBS, "mfmabench": mfma}))
 
 
 def main():

@@ -99,6 +99,13 @@ int obc_profile_end(obc_ctx *ctx, obc_kernel_stat stats[OBC_KERNEL_CLASSES]);
 int obc_membench(obc_ctx *ctx, int kind, int streaming, const void *src, void *dst, size_t bytes,
                  int reps, double *ms_per_pass);
 
+/* What the matrix cores of this GPU sustain on nothing but independent MFMA instructions, four
+ * wavefronts on every SIMD: kind 0 = v_mfma_f32_32x32x2_f32 (the Hessian's instruction), kind 1 =
+ * v_mfma_f64_16x16x4_f64 (the factorisation's).  Every wavefront issues 4 * iters instructions per
+ * pass; one warm-up pass and `reps` timed ones on the context's stream.  Returns the mean
+ * milliseconds per pass and the flops of a pass.  Synchronous. */
+int obc_mfmabench(obc_ctx *ctx, int kind, int iters, int reps, double *ms_per_pass, double *flops_per_pass);
+
 /* ---- Sec. 4: H = 2 X X^T, "Implementation Details": dampening -------------------------
  * X: d x N fp32 with leading dimension ldx >= N (element (j, n) at X[j*ldx + n]).
  * H: d x d fp32.  accumulate == 0: H = 2 X X^T;  accumulate != 0: H += 2 X X^T (calibration

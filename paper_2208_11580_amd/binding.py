@@ -25,7 +25,7 @@ SELECT_STATIC_MAX_WEIGHTS, SELECT_STATIC_MAX_ROWS = 2359296, 8192   # limits of 
 
 EXPORTS = [
     "obc_create", "obc_destroy", "obc_last_error", "obc_version", "obc_check",
-    "obc_profile_begin", "obc_profile_end", "obc_membench",
+    "obc_profile_begin", "obc_profile_end", "obc_membench", "obc_mfmabench",
     "obc_hessian_workspace_bytes", "obc_hessian",
     "obc_invert_workspace_bytes", "obc_invert",
     "obc_cross_workspace_bytes", "obc_cross", "obc_refit_workspace_bytes", "obc_refit",
@@ -73,6 +73,7 @@ def load_library():
     lib.obc_profile_begin.argtypes = [vp]
     lib.obc_profile_end.argtypes = [vp, POINTER(KernelStat)]
     lib.obc_membench.argtypes = [vp, c_int, c_int, vp, vp, c_size_t, c_int, POINTER(ctypes.c_double)]
+    lib.obc_mfmabench.argtypes = [vp, c_int, c_int, c_int, POINTER(ctypes.c_double), POINTER(ctypes.c_double)]
     lib.obc_hessian_workspace_bytes.argtypes = [c_int, c_int64, sp]
     lib.obc_hessian.argtypes = [vp, vp, c_int, c_int64, c_int64, c_float, c_int, vp, vp, c_size_t]
     lib.obc_invert_workspace_bytes.argtypes = [c_int, sp]
@@ -172,6 +173,12 @@ class Context:
         self._ck(self.lib.obc_profile_end(self.h, arr))
         return {name: dict(launches=arr[i].launches, ms=arr[i].ms, bytes=arr[i].bytes, flops=arr[i].flops)
                 for i, name in enumerate(KERNEL_CLASSES)}
+
+    def obc_mfmabench(self, kind, iters=20000, reps=3):
+        """TFLOP/s of a loop of independent fp32 (kind 0) / fp64 (kind 1) MFMA instructions."""
+        ms, fl = ctypes.c_double(), ctypes.c_double()
+        self._ck(self.lib.obc_mfmabench(self.h, int(kind), int(iters), int(reps), byref(ms), byref(fl)))
+        return fl.value / (ms.value * 1e-3) / 1e12
 
     def obc_membench(self, kind, src, dst, nbytes, reps=5, streaming=False):
         """Mean milliseconds per pass of the plain read (0) / write (1) / copy (2) kernel."""

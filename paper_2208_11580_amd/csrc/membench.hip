@@ -1,7 +1,9 @@
 // Measurement support: what this GPU's memory system gives the simplest possible kernels -- a pure
 // read, a pure write and a copy with 16-byte accesses -- so that the row solver's kernels, which are
 // bound by HBM traffic, can be compared with a ceiling measured on the same box rather than with the
-// data-sheet figure alone.  Not part of the method.
+// data-sheet figure alone; and what its matrix cores sustain on a loop of nothing but independent
+// MFMA instructions (the ceiling of the Hessian and of the fp64 factorisation kernels).  Not part of
+// the method.
 #include "common.h"
 
 namespace {
@@ -44,6 +46,46 @@ __global__ __launch_bounds__(256) void membench_kernel(const uintx4 *__restrict_
     }
     // the benchmark buffers are filled with words whose low bit is clear
     if (KIND == 0 && ((acc.x | acc.y | acc.z | acc.w) & 1u)) sink[0] = acc.x;
+}
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef double doublex4 __attribute__((ext_vector_type(4)));
+
+// `iters` rounds of four independent matrix-core instructions per wavefront (v_mfma_f32_32x32x2_f32 or
+// v_mfma_f64_16x16x4_f64); the sums are stored only if they take a value they cannot take
+template <bool F64>
+__global__ __launch_bounds__(256) void mfma_loop_kernel(int iters, unsigned *sink)
+{
+    const float a = 1e-3f * (float)(threadIdx.x & 63), b = 1.f + 1e-3f * (float)(threadIdx.x >> 6);
+    if (F64) {
+        doublex4 acc[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[q] = doublex4{0.0, 0.0, 0.0, 0.0};
+        for (int i = 0; i < iters; ++i) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[q] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a, (double)b, acc[q], 0, 0, 0);
+        }
+        double t = 0.0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) t += acc[q][0] + acc[q][1] + acc[q][2] + acc[q][3];
+        if (t == -1.0) sink[0] = 1u;
+    } else {
+        floatx16 acc[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[q][v] = 0.f;
+        for (int i = 0; i < iters; ++i) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[q], 0, 0, 0);
+        }
+        float t = 0.f;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) t += acc[q][v];
+        if (t == -1.f) sink[0] = 1u;
+    }
 }
 
 }  // namespace
@@ -90,5 +132,42 @@ extern "C" int obc_membench(obc_ctx *ctx, int kind, int streaming, const void *s
     if (err != hipSuccess) return obc_fail(ctx, OBC_ERR_HIP, "obc_membench: %s", hipGetErrorString(err));
     OBC_LAUNCH_CHECK(ctx, "membench_kernel");
     *ms_per_pass = (double)ms / reps;
+    return OBC_OK;
+}
+
+extern "C" int obc_mfmabench(obc_ctx *ctx, int kind, int iters, int reps, double *ms_per_pass, double *flops_per_pass)
+{
+    if (!ctx) return OBC_ERR_BAD_ARG;
+    if (kind < 0 || kind > 1 || iters < 1 || reps < 1 || !ms_per_pass || !flops_per_pass)
+        return obc_fail(ctx, OBC_ERR_BAD_ARG, "obc_mfmabench: bad argument");
+    int cus = 256;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, ctx->device) == hipSuccess && prop.multiProcessorCount > 0)
+        cus = prop.multiProcessorCount;
+    // four workgroups of four wavefronts per compute unit: four wavefronts on every SIMD
+    const unsigned blocks = (unsigned)cus * 4;
+    hipStream_t st = ctx->stream;
+    unsigned *sink = (unsigned *)ctx->d_status + 32;
+    hipEvent_t e0, e1;
+    OBC_HIP(ctx, hipEventCreate(&e0));
+    OBC_HIP(ctx, hipEventCreate(&e1));
+    auto launch = [&]() {
+        if (kind == 1) mfma_loop_kernel<true><<<blocks, 256, 0, st>>>(iters, sink);
+        else mfma_loop_kernel<false><<<blocks, 256, 0, st>>>(iters, sink);
+    };
+    launch();                                     // warm-up (clocks)
+    (void)hipEventRecord(e0, st);
+    for (int r = 0; r < reps; ++r) launch();
+    (void)hipEventRecord(e1, st);
+    hipError_t err = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (err == hipSuccess) err = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (err != hipSuccess) return obc_fail(ctx, OBC_ERR_HIP, "obc_mfmabench: %s", hipGetErrorString(err));
+    OBC_LAUNCH_CHECK(ctx, "mfma_loop_kernel");
+    *ms_per_pass = (double)ms / reps;
+    // 2 * M * N * K flops per instruction: 32 x 32 x 2 (fp32), 16 x 16 x 4 (fp64)
+    *flops_per_pass = (double)blocks * 4.0 * (double)iters * 4.0 * (kind == 1 ? 2048.0 : 4096.0);
     return OBC_OK;
 }

@@ -640,6 +640,18 @@ def test_membench_kernels_move_what_they_say(obc):
         obc.obc_membench(2, src, dst, 24, reps=1)              # not a multiple of 16 bytes
 
 
+def test_mfmabench_stays_below_the_data_sheet(obc):
+    """The loop of independent MFMA instructions runs and reports a rate no matrix core can exceed."""
+    f32 = obc.obc_mfmabench(0, iters=2000, reps=2)
+    f64 = obc.obc_mfmabench(1, iters=2000, reps=2)
+    print("fp32 MFMA %.1f TFLOP/s, fp64 MFMA %.1f TFLOP/s" % (f32, f64))
+    assert 10.0 < f32 < 157.3 * 1.05
+    assert 5.0 < f64 < 78.6 * 1.05
+    import paper_2208_11580_amd as pkg
+    with pytest.raises(pkg.ObcError):
+        obc.obc_mfmabench(2)
+
+
 def test_trace_of_an_odd_width_is_fully_written(obc, orc):
     # the trace is cleared by a 16-byte-wide fill before the steps scatter into it: a size that is
     # no multiple of four floats, over memory that held NaNs before
