@@ -56,6 +56,7 @@ int main()
     EXPECT(obc_profile_begin(nullptr) == OBC_ERR_BAD_ARG);
     EXPECT(obc_profile_end(nullptr, nullptr) == OBC_ERR_BAD_ARG);
     EXPECT(obc_membench(nullptr, 0, 0, &f, &f, 16, 1, &ms) == OBC_ERR_BAD_ARG);
+    EXPECT(obc_mfmabench(nullptr, 0, 1, 1, &ms, &ms) == OBC_ERR_BAD_ARG);
     EXPECT(obc_hessian(nullptr, &f, 1, 1, 1, 0.f, 0, &f, &f, 4) == OBC_ERR_BAD_ARG);
     EXPECT(obc_invert(nullptr, &f, 1, &f, 4) == OBC_ERR_BAD_ARG);
     EXPECT(obc_cross(nullptr, &f, &f, 1, 1, 1, 1, 1, 0, &f, &f, 4) == OBC_ERR_BAD_ARG);
