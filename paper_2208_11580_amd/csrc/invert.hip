@@ -192,6 +192,56 @@ __global__ __launch_bounds__(256) void yty_kernel(const double *__restrict__ Y, 
     });
 }
 
+// C (M x N, row-major) = A B over k in a range that skips known zeros, in 64 x 64 tiles with 64-deep
+// slabs requested two ahead (as yty_kernel).  A is row-major (M x K, leading dimension lda); B is
+// either B_T: given as its transpose (b(k, j) = Bt[j][k]; with `tri` the rows of Bt are those of a
+// lower triangular matrix, so k stops at the end of the tile's last column) or plain (b(k, j) =
+// B[k][j]; with `tri` B is lower triangular and k starts at the tile's first column).
+template <bool B_T>
+__global__ __launch_bounds__(256) void slab_gemm_kernel(const double *__restrict__ A, int64_t lda,
+                                                        const double *__restrict__ B, int64_t ldb,
+                                                        double *__restrict__ C, int64_t ldc, int M, int N, int K, int tri)
+{
+    __shared__ double lds[2 * NB * PL];
+    double *As = lds, *Bs = lds + NB * PL;
+    const int i0 = blockIdx.y * NB, j0 = blockIdx.x * NB;
+    if (i0 >= M || j0 >= N) return;
+    const int Mi = (M - i0 < NB) ? M - i0 : NB, Nj = (N - j0 < NB) ? N - j0 : NB;
+    const int kbeg = (!B_T && tri) ? j0 : 0;
+    const int kend = (B_T && tri && j0 + NB < K) ? j0 + NB : K;
+    doublex4 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) acc[a][b] = doublex4{0.0, 0.0, 0.0, 0.0};
+    double ra[2][16], rb[2][16];
+    auto fetch = [&](int k0, double (&fa)[16], double (&fb)[16]) {
+        const int kr = (kend - k0 < NB) ? kend - k0 : NB;
+        tile_fetch(fa, A + (int64_t)i0 * lda + k0, lda, Mi, kr);                  // (i, k)
+        if (B_T) tile_fetch(fb, B + (int64_t)j0 * ldb + k0, ldb, Nj, kr);         // (j, k)
+        else tile_fetch(fb, B + (int64_t)k0 * ldb + j0, ldb, kr, Nj);             // (k, j)
+    };
+    auto slab = [&](int knext, double (&fa)[16], double (&fb)[16]) {
+        tile_park<true>(As, fa);
+        if (B_T) tile_park<true>(Bs, fb);
+        else tile_park<false>(Bs, fb);
+        __syncthreads();
+        if (knext < kend) fetch(knext, fa, fb);
+        tile_mma<true>(acc, As, Bs);
+        __syncthreads();
+    };
+    fetch(kbeg, ra[0], rb[0]);
+    if (kbeg + NB < kend) fetch(kbeg + NB, ra[1], rb[1]);
+    for (int k0 = kbeg; k0 < kend; k0 += 2 * NB) {
+        slab(k0 + 2 * NB, ra[0], rb[0]);
+        if (k0 + NB >= kend) break;
+        slab(k0 + 3 * NB, ra[1], rb[1]);
+    }
+    tile_each(acc, [&](int i, int j, double v) {
+        if (i < Mi && j < Nj) C[(int64_t)(i0 + i) * ldc + j0 + j] = v;
+    });
+}
+
 // The diagonal-block factorisation of potrf_wave for a whole workgroup of four wavefronts, block
 // already in LDS (layout and contract of potrf_wave_core; the factor is not written out).  The 64
 // dependent column steps stay on wavefront 0, everything else moves off its chain:
@@ -654,8 +704,8 @@ int obc_refit(obc_ctx *ctx, float *H, int d_col, const float *C, int d_row, floa
     const int64_t n = (int64_t)R * d;
     f32_to_f64_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(C, C64, n);
     // W = C H^-1 = (C Y^T) Y with Y = L^-1: both products in fp64
-    gemm64_kernel<<<grid64(R, d), 256, 0, st>>>(mk(R, d, d, 1.0, C64, d, 1, Y, 1, d, 0.0, T1, d, 0, 0, nullptr));
-    gemm64_kernel<<<grid64(R, d), 256, 0, st>>>(mk(R, d, d, 1.0, T1, d, 1, Y, d, 1, 0.0, C64, d, 0, 1, nullptr));
+    slab_gemm_kernel<true><<<grid64(R, d), 256, 0, st>>>(C64, d, Y, d, T1, d, R, d, d, 1);     // T1 = C Y^T
+    slab_gemm_kernel<false><<<grid64(R, d), 256, 0, st>>>(T1, d, Y, d, C64, d, R, d, d, 1);    // W = T1 Y
     f64_to_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(C64, W_out, n);
     OBC_LAUNCH_CHECK(ctx, "refit kernels");
     if (invert_in_place) {
